@@ -1,0 +1,185 @@
+/*
+ * TEST INFRASTRUCTURE -- not part of the product path.
+ *
+ * Plain CPU oracle for the per-step gradient synchronisation of K bulk-synchronous
+ * data-parallel workers that run with different per-worker batch sizes (paper: Background,
+ * "Distributed machine learning systems"; Problem Formulation, "Action space and batch size
+ * adjustment"; Algorithm 1, the step "compute gradient g_i and update global model" and the
+ * following "collect performance metrics" step), together with the gradient statistics that
+ * the agent's state and reward use (Problem Formulation, "Training Statistical Efficiency
+ * Metrics": sigma_norm and sigma_norm^2; reward term -eta(sigma_norm^2 + sigma_norm)) and the
+ * gradient noise scale the evaluation leans on (Evaluation, discussion of the batch size
+ * trajectories).
+ *
+ * The paper names these quantities but prints no formula for any of them.  The definitions
+ * below are the standard estimators, written out directly:
+ *
+ *   B      = sum_k b_k
+ *   G_i    = (sum_k b_k g_ki) / B                     weighted mean over the global batch
+ *   n_k    = sum_i g_ki^2                             per-worker squared norm
+ *   A      = sum_i G_i^2                              squared norm of the aggregate
+ *   d_k    = sum_i (g_ki - G_i)^2                     per-worker squared deviation
+ *   T      = (sum_k b_k d_k) / (K-1),  0 when K == 1  unbiased tr(Sigma) of the per-example
+ *                                                     gradient covariance
+ *   A_unb  = A - T/B                                  unbiased |mu|^2
+ *   noise_scale        = T / A_unb
+ *   noise_scale_biased = T / A
+ *   sigma2_norm        = T / (B A)                    variance of the applied update over its
+ *                                                     squared norm (reading of sigma_norm^2;
+ *                                                     parity against the paper itself: unpinned,
+ *                                                     because the paper gives no formula)
+ *   sigma_norm         = sqrt(max(0, sigma2_norm))
+ *
+ * Every record is this definition restricted to an index range [lo, hi): record 0 is the whole
+ * vector, records 1..S are the caller's contiguous segments (layers).  The global record is
+ * summed directly over [0, P), never by adding segment records.
+ *
+ * Arithmetic: inputs are widened exactly (fp32 and bf16 are subsets of double); every sum over
+ * i is carried in an x87 80-bit long double accumulator, so the oracle's own rounding error is
+ * ~1e-16 relative even over 1e8 terms.  No blocking, no fusion: one loop over i, an inner loop
+ * over k.  With threads > 1 the index range is cut into `threads` equal consecutive blocks, each
+ * summed by the same loop, and the block sums are added in block order (only used to make the
+ * full-size checks and the timed baseline finish quickly; threads == 1 is the plain loop).
+ */
+#include <float.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#if LDBL_MANT_DIG < 64
+#error "oracle needs an extended-precision long double"
+#endif
+
+typedef long double acc_t;
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_HEAD = 8 }; /* scalars in front of the per-worker entries of a record */
+
+static inline double widen(const void *base, int dtype, int64_t i)
+{
+    if (dtype == ORACLE_F32)
+        return (double)((const float *)base)[i];
+    /* bf16 is the upper half of the fp32 encoding */
+    uint32_t bits = (uint32_t)((const uint16_t *)base)[i] << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+/* raw sums of one consecutive block: sums[0]=A, sums[1..K]=n_k, sums[1+K..2K]=d_k */
+static void block_sums(const void *const *g, const int32_t *b, int K, int dtype, int64_t lo,
+                       int64_t hi, acc_t B, acc_t *sums, double *agg)
+{
+    acc_t *n = sums + 1, *d = sums + 1 + K;
+    for (int j = 0; j < 2 * K + 1; ++j)
+        sums[j] = 0;
+    for (int64_t i = lo; i < hi; ++i) {
+        acc_t s = 0;
+        for (int k = 0; k < K; ++k)
+            s += (acc_t)b[k] * (acc_t)widen(g[k], dtype, i);
+        acc_t G = s / B;
+        sums[0] += G * G;
+        for (int k = 0; k < K; ++k) {
+            acc_t x = (acc_t)widen(g[k], dtype, i);
+            n[k] += x * x;
+            d[k] += (x - G) * (x - G);
+        }
+        if (agg)
+            agg[i] = (double)G;
+    }
+}
+
+static int record(const void *const *g, const int32_t *b, int K, int dtype, int64_t lo,
+                  int64_t hi, int threads, double *agg, double *rec)
+{
+    const int W = 2 * K + 1;
+    acc_t B = 0;
+    for (int k = 0; k < K; ++k)
+        B += (acc_t)b[k];
+    if (threads < 1)
+        threads = 1;
+    if ((int64_t)threads > hi - lo)
+        threads = (int)(hi - lo);
+    acc_t *part = (acc_t *)malloc(sizeof(acc_t) * (size_t)W * (size_t)threads);
+    if (!part)
+        return 1;
+#pragma omp parallel for schedule(static) num_threads(threads)
+    for (int t = 0; t < threads; ++t) {
+        int64_t len = hi - lo;
+        int64_t b0 = lo + (int64_t)(((__int128)len * t) / threads);
+        int64_t b1 = lo + (int64_t)(((__int128)len * (t + 1)) / threads);
+        block_sums(g, b, K, dtype, b0, b1, B, part + (size_t)W * t, agg);
+    }
+    for (int t = 1; t < threads; ++t) /* block order */
+        for (int j = 0; j < W; ++j)
+            part[j] += part[(size_t)W * t + j];
+
+    acc_t A = part[0], wd = 0;
+    for (int k = 0; k < K; ++k)
+        wd += (acc_t)b[k] * part[1 + K + k];
+    acc_t T = (K > 1) ? wd / (acc_t)(K - 1) : 0;
+    acc_t A_unb = A - T / B;
+    acc_t s2 = T / (B * A);
+    rec[0] = (double)A;
+    rec[1] = (double)T;
+    rec[2] = (double)A_unb;
+    rec[3] = (double)(T / A_unb);
+    rec[4] = (double)(T / A);
+    rec[5] = (double)s2;
+    rec[6] = (double)sqrtl(s2 > 0 ? s2 : 0); /* NaN compares false and maps to 0 */
+    rec[7] = (double)(hi - lo);
+    for (int k = 0; k < K; ++k) {
+        rec[ORACLE_HEAD + k] = (double)part[1 + k];
+        rec[ORACLE_HEAD + K + k] = (double)part[1 + K + k];
+    }
+    free(part);
+    return 0;
+}
+
+/*
+ * grads: K host pointers, each P elements of dtype (0 = fp32, 1 = bf16 as uint16).
+ * b: K positive batch sizes.  offsets: S+1 strictly increasing entries, offsets[0] == 0,
+ * offsets[S] == P, or NULL with S == 0 (global record only).
+ * agg: P doubles or NULL.  stats: (1+S) * (8+2K) doubles.
+ * Returns 0, or 1 on an invalid argument / allocation failure.
+ */
+int dynamix_oracle_aggregate_stats(const void *const *grads, const int32_t *b, int32_t K,
+                                   int64_t P, int32_t dtype, const int64_t *offsets, int64_t S,
+                                   double *agg, double *stats, int32_t threads)
+{
+    if (!grads || !b || !stats || K < 1 || P < 1 || (dtype != ORACLE_F32 && dtype != ORACLE_BF16))
+        return 1;
+    for (int k = 0; k < K; ++k)
+        if (!grads[k] || b[k] <= 0)
+            return 1;
+    if (offsets) {
+        if (S < 1 || offsets[0] != 0 || offsets[S] != P)
+            return 1;
+        for (int64_t j = 0; j < S; ++j)
+            if (offsets[j + 1] <= offsets[j])
+                return 1;
+    } else if (S != 0) {
+        return 1;
+    }
+    const int R = ORACLE_HEAD + 2 * K;
+    if (record(grads, b, K, dtype, 0, P, threads, agg, stats))
+        return 1;
+    for (int64_t j = 0; j < S; ++j)
+        if (record(grads, b, K, dtype, offsets[j], offsets[j + 1], threads, NULL,
+                   stats + (size_t)R * (size_t)(j + 1)))
+            return 1;
+    return 0;
+}
+
+int dynamix_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

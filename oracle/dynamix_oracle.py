@@ -1,0 +1,106 @@
+"""TEST INFRASTRUCTURE -- ctypes front end of the plain C oracle (dynamix_oracle.c).
+
+Marshals numpy arrays into the C function and compiles it with gcc when the shared object is
+missing or older than the source.  Holds none of the method's arithmetic.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dynamix_oracle.c")
+_LIB = os.path.join(_HERE, "libdynamix_oracle.so")
+
+HEAD = 8
+#: positions of the scalars in a statistics record (the per-worker entries follow at HEAD)
+IDX = {
+    "agg_sqnorm": 0,
+    "tr_sigma": 1,
+    "agg_sqnorm_unbiased": 2,
+    "noise_scale": 3,
+    "noise_scale_biased": 4,
+    "sigma2_norm": 5,
+    "sigma_norm": 6,
+    "count": 7,
+}
+
+_lib = None
+
+
+def build(force=False):
+    """Compile the C oracle into oracle/libdynamix_oracle.so."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        lib.dynamix_oracle_aggregate_stats.restype = ctypes.c_int
+        lib.dynamix_oracle_aggregate_stats.argtypes = [
+            ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
+            ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64), ctypes.c_int64,
+            ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), ctypes.c_int32]
+        lib.dynamix_oracle_max_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def max_threads():
+    return int(_load().dynamix_oracle_max_threads())
+
+
+def stats_count(K, S):
+    return (1 + S) * (HEAD + 2 * K)
+
+
+def aggregate_stats(grads, batch_sizes, segment_offsets=None, want_agg=True, threads=1):
+    """Run the oracle.
+
+    grads: K one-dimensional numpy arrays of equal length, dtype float32, or uint16 holding
+    bf16 bit patterns.  batch_sizes: K positive integers.  segment_offsets: None, or S+1
+    increasing offsets from 0 to P.
+    Returns (agg, stats): agg is float64[P] (None if not wanted), stats is float64[1+S, 8+2K].
+    """
+    lib = _load()
+    K = len(grads)
+    if K < 1:
+        raise ValueError("need at least one worker")
+    arrs = [np.ascontiguousarray(g) for g in grads]
+    dt = arrs[0].dtype
+    if dt == np.float32:
+        code = 0
+    elif dt == np.uint16:
+        code = 1
+    else:
+        raise TypeError("gradients must be float32 or uint16 (bf16 bits), got %s" % dt)
+    P = arrs[0].shape[0]
+    for a in arrs:
+        if a.ndim != 1 or a.shape[0] != P or a.dtype != dt:
+            raise ValueError("all worker gradients must be 1-d, same length and dtype")
+    ptrs = (ctypes.c_void_p * K)(*[a.ctypes.data for a in arrs])
+    b = np.ascontiguousarray(np.asarray(batch_sizes, dtype=np.int32))
+    if b.shape != (K,):
+        raise ValueError("batch_sizes must have one entry per worker")
+    if segment_offsets is None:
+        S, off_p, off = 0, None, None
+    else:
+        off = np.ascontiguousarray(np.asarray(segment_offsets, dtype=np.int64))
+        S = off.shape[0] - 1
+        off_p = off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+    agg = np.empty(P, dtype=np.float64) if want_agg else None
+    stats = np.empty((1 + S, HEAD + 2 * K), dtype=np.float64)
+    rc = lib.dynamix_oracle_aggregate_stats(
+        ptrs, b.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), K, P, code, off_p, S,
+        agg.ctypes.data_as(ctypes.POINTER(ctypes.c_double)) if want_agg else None,
+        stats.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), int(threads))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return agg, stats
