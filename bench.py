@@ -1,0 +1,138 @@
+"""Throughput of the gradient aggregate + statistics hot path on one MI355X.
+
+A step is one call of dynamix_grad_aggregate_stats_ex (streaming pass + final reduction) over the
+K gradient buffers of one synthetic workload, all resident in HBM before the timed region.
+Prints one JSON line: gradient GB/s processed (K*P*sizeof(dtype) per step), the roofline figures
+of the dominant kernel measured with HIP events recorded around it on its own stream, and the
+CPU oracle timed on a bounded sample of the same inputs on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+
+def describe(w):
+    seg = "single segment" if w.S == 0 else "%d segments" % w.S
+    dt = "bf16" if w.itemsize == 2 else "fp32"
+    return "%s: K=%d workers, P=%d %s gradients, %s" % (w.name, w.K, w.P, dt, seg)
+
+
+def cpu_baseline(w, sample_elems, threads):
+    """Times the CPU oracle, as it stands, on the first `sample_elems` elements of every worker
+    buffer (copied to the host outside the timed part)."""
+    import oracle
+    n = min(sample_elems, w.P)
+    off = None
+    if w.segment_offsets is not None:
+        off = [int(o) for o in w.segment_offsets if o < n] + [n]
+    host = w.host_arrays(0, n)
+    threads = max(1, min(threads, oracle.max_threads()))
+    t0 = time.perf_counter()
+    oracle.aggregate_stats(host, w.batch_sizes, off, want_agg=True, threads=threads)
+    dt = time.perf_counter() - t0
+    nbytes = w.K * n * w.itemsize
+    return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d of %d elements of each of the %d worker buffers "
+                      "(%.3f GB read, %.2f s wall)" % (n, w.P, w.K, nbytes / 1e9, dt),
+            "elements_per_s": w.K * n / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--cpu-sample", type=int, default=16_000_000,
+                    help="elements per worker the CPU oracle is timed on (0: skip)")
+    ap.add_argument("--cpu-threads", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this path runs on one GPU only (no sharding, no collectives); "
+                 "run with --gpus 1")
+
+    import torch
+    import paper_2510_08522_amd as D
+    from paper_2510_08522_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    D.binding.load()                      # fails loudly if the HIP library is not built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = W.config(args.workload, device=dev)
+    out_agg = torch.empty(w.P, dtype=torch.float32, device=dev)
+    out_stats = torch.empty((1 + w.S, D.DYNAMIX_STATS_HEAD + 2 * w.K), dtype=torch.float64,
+                            device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        D.dynamix_grad_aggregate_stats_ex(w.grads, w.batch_sizes, w.segment_offsets,
+                                          out_agg=out_agg, out_stats=out_stats, stream=stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    D.dynamix_timing_begin(args.steps)    # event slots are created outside the timed region
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    n = D.dynamix_timing_count()
+    times = [D.dynamix_timing_read(i) for i in range(n)]
+    D.dynamix_timing_begin(0)
+    k_stream = sum(t[0] for t in times) / n * 1e-3      # seconds per launch
+    k_final = sum(t[1] for t in times) / n * 1e-3
+
+    ms_per_step = elapsed / args.steps * 1e3
+    read_bytes = w.bytes_read
+    algo_bytes = read_bytes + w.P * 4                    # K*s read + 4 written per element
+    value = read_bytes / (elapsed / args.steps) / 1e9
+    achieved = algo_bytes / k_stream / 1e9
+    ns = float(out_stats[0, D.STAT["noise_scale"]].item())
+
+    line = {
+        "metric": "gradient GB/s processed (aggregate+stats)",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",      # accumulation type; bf16 inputs are widened exactly
+        "data": "synthetic",
+        "config": {"workload": describe(w), "K": w.K, "P": w.P, "segments": w.S,
+                   "input_dtype": "bf16" if w.itemsize == 2 else "fp32",
+                   "bytes_read_per_step": read_bytes, "seed": w.seed},
+        "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "elements_per_s": w.K * w.P / (elapsed / args.steps),
+        "total_traffic_GBps": round(algo_bytes / (elapsed / args.steps) / 1e9, 2),
+        "noise_scale": ns,
+        "roofline": {"bound": "hbm", "kernel": "stream_pass_kernel",
+                     "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "algorithmic_bytes_per_launch": algo_bytes,
+                     "kernel_ms": round(k_stream * 1e3, 5),
+                     "final_reduce_ms": round(k_final * 1e3, 5)},
+    }
+    if args.cpu_sample > 0:
+        line["cpu_baseline"] = cpu_baseline(w, args.cpu_sample, args.cpu_threads)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

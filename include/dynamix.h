@@ -1,0 +1,145 @@
+/*
+ * dynamix.h -- C ABI of the per-step gradient aggregate + statistics path on one MI355X.
+ *
+ * Setting (paper: Background, "Distributed machine learning systems"; Problem Formulation,
+ * "Action space and batch size adjustment"; Algorithm 1, the steps "compute gradient g_i and
+ * update global model" and "collect performance metrics"): K bulk-synchronous data-parallel
+ * workers hold a full model replica each, worker k computes its gradient g_k on a batch of its
+ * own size b_k (an integer the agent moves inside [32, 1024]), and at the barrier the gradients
+ * are combined.  The agent's state carries gradient statistics (Problem Formulation, "Training
+ * Statistical Efficiency Metrics": sigma_norm, sigma_norm^2; reward term
+ * -eta (sigma_norm^2 + sigma_norm)).  The paper prints no formula for the combination or the
+ * statistics; this library uses the mean over the global batch and the standard estimators:
+ *
+ *   B = sum_k b_k            G_i = (sum_k b_k g_ki) / B
+ *   n_k = sum_i g_ki^2       A = sum_i G_i^2       d_k = sum_i (g_ki - G_i)^2
+ *   T = (sum_k b_k d_k)/(K-1)   (0 when K == 1; unbiased trace of the per-example covariance)
+ *
+ * One call makes a single streaming pass over the K gradient buffers and produces G and one
+ * statistics record for the whole vector plus one per caller-defined contiguous segment
+ * (layer).  Everything runs in HIP kernels enqueued on the caller's stream; the call never
+ * synchronises the device or the stream.
+ *
+ * Plain C: no C++ types and no exceptions cross this boundary.
+ */
+#ifndef DYNAMIX_H
+#define DYNAMIX_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Storage type of the gradient buffers.  Accumulation is fp32 per lane and fp64 across blocks
+ * for both; the aggregate is always written as fp32. */
+typedef enum { DYNAMIX_F32 = 0, DYNAMIX_BF16 = 1 } dynamix_dtype;
+
+typedef enum {
+    DYNAMIX_OK = 0,
+    DYNAMIX_ERR_NULL = 1,     /* a required pointer (or one of the K gradient pointers) is NULL */
+    DYNAMIX_ERR_ARG = 2,      /* K < 1, K > DYNAMIX_K_MAX, P < 1, a batch size <= 0, bad dtype */
+    DYNAMIX_ERR_SEGMENTS = 3, /* offsets do not start at 0, are not strictly increasing, or do not end at P */
+    DYNAMIX_ERR_ALIGN = 4,    /* a gradient pointer or out_agg is not 16-byte aligned, or out_stats not 8-byte */
+    DYNAMIX_ERR_NOMEM = 5,    /* the library could not allocate its workspace */
+    DYNAMIX_ERR_HIP = 6       /* a HIP runtime call failed (launch, copy, device query) */
+} dynamix_status;
+
+enum { DYNAMIX_K_MAX = 64 };        /* most workers per call: pointers and weights travel in the kernel arguments */
+enum { DYNAMIX_STATS_HEAD = 8 };    /* scalars in front of the per-worker entries of a record */
+
+/* Positions inside one statistics record of DYNAMIX_STATS_HEAD + 2K doubles. */
+enum {
+    DYNAMIX_STAT_AGG_SQNORM = 0,          /* A = sum_i G_i^2 */
+    DYNAMIX_STAT_TR_SIGMA = 1,            /* T */
+    DYNAMIX_STAT_AGG_SQNORM_UNBIASED = 2, /* A - T/B, unbiased |E g|^2 */
+    DYNAMIX_STAT_NOISE_SCALE = 3,         /* T / (A - T/B); IEEE division, never clamped */
+    DYNAMIX_STAT_NOISE_SCALE_BIASED = 4,  /* T / A */
+    DYNAMIX_STAT_SIGMA2_NORM = 5,         /* T / (B A): variance of G over its squared norm */
+    DYNAMIX_STAT_SIGMA_NORM = 6,          /* sqrt(max(0, sigma2_norm)) */
+    DYNAMIX_STAT_COUNT = 7                /* elements covered by the record */
+    /* [8 .. 8+K)     worker_sqnorm[k]     = n_k
+       [8+K .. 8+2K)  worker_dev_sqnorm[k] = d_k */
+};
+
+/*
+ * Weighted aggregation of K workers' gradients fused with the statistics above
+ * (Algorithm 1: gradient synchronisation and metric collection of one training iteration).
+ *
+ * grads            HOST array of K DEVICE pointers.  grads[k] holds P elements of `dtype`,
+ *                  contiguous, 16-byte aligned, read-only for the call, owned by the caller.
+ *                  The K buffers are independent allocations; none may overlap out_agg.
+ * batch_sizes      HOST array of K per-worker batch sizes b_k, each > 0.
+ * K, P             number of workers (1..DYNAMIX_K_MAX) and elements per gradient (>= 1).
+ * dtype            a dynamix_dtype.
+ * segment_offsets  HOST array, or NULL.  NULL: one record for [0, P) only.  Otherwise strictly
+ *                  increasing element offsets that start at 0; the array ends at the first
+ *                  entry equal to P (S+1 entries for S segments; segments need no alignment).
+ * out_agg          DEVICE, P floats, 16-byte aligned, caller-owned; receives G.  NULL skips
+ *                  the write (statistics only).
+ * out_stats        DEVICE, dynamix_stats_count(K, S) doubles, caller-owned.  Record 0 covers
+ *                  [0, P); records 1..S the segments (present only with segment_offsets).
+ * stream           a hipStream_t passed as void*; NULL is the default stream.
+ *
+ * Host arrays are consumed before the call returns.  Arguments are validated before the first
+ * HIP call; on any error nothing is enqueued and a dynamix_status other than DYNAMIX_OK is
+ * returned.  Results are valid once the caller has synchronised `stream`.  Non-finite inputs
+ * propagate by IEEE rules.  The library keeps a small workspace per (device, stream, shape),
+ * allocated on the first call with that shape and reused afterwards; two calls that share it
+ * must be ordered on that stream.  For fixed inputs, shape and device the results are bitwise
+ * reproducible (fixed-order reductions, no atomics).
+ */
+int dynamix_grad_aggregate_stats(const void* const* grads, const int32_t* batch_sizes,
+                                 int32_t K, int64_t P, int32_t dtype,
+                                 const int64_t* segment_offsets, float* out_agg,
+                                 double* out_stats, void* stream);
+
+/* Same operation with the number of segments given explicitly: segment_offsets holds
+ * num_segments + 1 entries (num_segments == 0 requires segment_offsets == NULL). */
+int dynamix_grad_aggregate_stats_ex(const void* const* grads, const int32_t* batch_sizes,
+                                    int32_t K, int64_t P, int32_t dtype,
+                                    const int64_t* segment_offsets, int64_t num_segments,
+                                    float* out_agg, double* out_stats, void* stream);
+
+/* Doubles needed for out_stats: (1 + S) * (DYNAMIX_STATS_HEAD + 2K); S = 0 without segments.
+ * Returns -1 for K outside 1..DYNAMIX_K_MAX or S < 0. */
+int64_t dynamix_stats_count(int32_t K, int64_t num_segments);
+
+/*
+ * Diagnostic, pure host arithmetic (no HIP call, usable without a GPU): the work decomposition
+ * the library uses for this shape on a device that keeps `max_blocks` blocks resident.
+ * The range of 16-byte vectors is dealt to blocks as contiguous spans (or, with interleave != 0
+ * and no segments, tile-by-tile round robin) and cut at segment boundaries into pieces; each
+ * piece yields one partial statistics record.  Up to `capacity` pieces are written to
+ * pieces_out as six int64 each: first vector, end vector, vector step per block iteration,
+ * first element, end element (elements outside are masked), owning block.  A vector holds 4
+ * fp32 or 8 bf16 elements.  Returns the number of pieces, or minus a dynamix_status.
+ */
+int64_t dynamix_plan_describe(int32_t K, int64_t P, int32_t dtype, const int64_t* segment_offsets,
+                              int64_t num_segments, int64_t max_blocks, int32_t interleave,
+                              int64_t* pieces_out, int64_t capacity);
+
+/* Static, NUL-terminated description of a dynamix_status value. */
+const char* dynamix_status_string(int status);
+
+/*
+ * Kernel timing (profiling aid).  dynamix_timing_begin(capacity) creates `capacity` slots of HIP
+ * events (capacity 0 switches timing off and frees them).  While slots remain, every call to the
+ * aggregate entry points records three events on its stream: before the streaming pass, between
+ * the two kernels, after the final reduction.  dynamix_timing_count() is the number of slots
+ * used.  Once the stream has been synchronised, dynamix_timing_read(i, ...) returns the two
+ * kernel durations of the i-th timed call in milliseconds (DYNAMIX_ERR_HIP if that call has not
+ * finished, DYNAMIX_ERR_ARG for an unused slot).
+ */
+int     dynamix_timing_begin(int32_t capacity);
+int32_t dynamix_timing_count(void);
+int     dynamix_timing_read(int32_t index, float* stream_pass_ms, float* final_reduce_ms);
+
+/* Frees every cached plan and workspace.  The caller must have synchronised all streams that
+ * were used with the library.  Returns a dynamix_status. */
+int dynamix_release_cached(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNAMIX_H */

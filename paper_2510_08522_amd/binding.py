@@ -1,0 +1,187 @@
+"""ctypes binding of libdynamix.so: argument marshalling only.
+
+Every step of the path (aggregation, statistics, reductions, derived scalars) runs in the HIP
+kernels behind the C ABI declared in include/dynamix.h; torch is used for device memory and
+streams.  There is no CPU fallback: a missing library raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdynamix.so")
+
+DYNAMIX_F32, DYNAMIX_BF16 = 0, 1
+DYNAMIX_OK = 0
+DYNAMIX_ERR_NULL, DYNAMIX_ERR_ARG, DYNAMIX_ERR_SEGMENTS = 1, 2, 3
+DYNAMIX_ERR_ALIGN, DYNAMIX_ERR_NOMEM, DYNAMIX_ERR_HIP = 4, 5, 6
+DYNAMIX_K_MAX = 64
+DYNAMIX_STATS_HEAD = 8
+STAT = {"agg_sqnorm": 0, "tr_sigma": 1, "agg_sqnorm_unbiased": 2, "noise_scale": 3,
+        "noise_scale_biased": 4, "sigma2_norm": 5, "sigma_norm": 6, "count": 7}
+
+_lib = None
+
+
+class DynamixError(RuntimeError):
+    def __init__(self, status):
+        self.status = int(status)
+        super().__init__("dynamix: %s (status %d)" % (dynamix_status_string(status), status))
+
+
+def load():
+    """Load libdynamix.so from the package directory; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libdynamix.so is not built: run `python -m paper_2510_08522_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.dynamix_grad_aggregate_stats.restype = ctypes.c_int
+    lib.dynamix_grad_aggregate_stats.argtypes = [vp, vp, i32, i64, i32, vp, vp, vp, vp]
+    lib.dynamix_grad_aggregate_stats_ex.restype = ctypes.c_int
+    lib.dynamix_grad_aggregate_stats_ex.argtypes = [vp, vp, i32, i64, i32, vp, i64, vp, vp, vp]
+    lib.dynamix_stats_count.restype = i64
+    lib.dynamix_stats_count.argtypes = [i32, i64]
+    lib.dynamix_status_string.restype = ctypes.c_char_p
+    lib.dynamix_status_string.argtypes = [ctypes.c_int]
+    lib.dynamix_plan_describe.restype = i64
+    lib.dynamix_plan_describe.argtypes = [i32, i64, i32, vp, i64, i64, i32, vp, i64]
+    lib.dynamix_timing_begin.restype = ctypes.c_int
+    lib.dynamix_timing_begin.argtypes = [i32]
+    lib.dynamix_timing_count.restype = i32
+    lib.dynamix_timing_count.argtypes = []
+    lib.dynamix_timing_read.restype = ctypes.c_int
+    lib.dynamix_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_float),
+                                        ctypes.POINTER(ctypes.c_float)]
+    lib.dynamix_release_cached.restype = ctypes.c_int
+    lib.dynamix_release_cached.argtypes = []
+    _lib = lib
+    return lib
+
+
+def dynamix_stats_count(K, num_segments):
+    return int(load().dynamix_stats_count(int(K), int(num_segments)))
+
+
+def dynamix_status_string(status):
+    return load().dynamix_status_string(int(status)).decode()
+
+
+def dynamix_release_cached():
+    return int(load().dynamix_release_cached())
+
+
+def dynamix_plan_describe(K, P, dtype, segment_offsets=None, max_blocks=512, interleave=False):
+    """The work decomposition for a shape as an int64 array [pieces, 6]:
+    (first vector, end vector, vector step, first element, end element, block).  Host only."""
+    lib = load()
+    off, S = None, 0
+    if segment_offsets is not None:
+        S = len(segment_offsets) - 1
+        off = (ctypes.c_int64 * (S + 1))(*[int(x) for x in segment_offsets])
+    n = lib.dynamix_plan_describe(K, P, dtype, off, S, max_blocks, int(interleave), None, 0)
+    if n < 0:
+        raise DynamixError(-n)
+    out = np.zeros((n, 6), dtype=np.int64)
+    lib.dynamix_plan_describe(K, P, dtype, off, S, max_blocks, int(interleave),
+                              out.ctypes.data_as(ctypes.c_void_p), n)
+    return out
+
+
+def dynamix_timing_begin(capacity):
+    rc = int(load().dynamix_timing_begin(int(capacity)))
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+
+
+def dynamix_timing_count():
+    return int(load().dynamix_timing_count())
+
+
+def dynamix_timing_read(index):
+    """(streaming pass ms, final reduction ms) of the index-th timed call; sync the stream first."""
+    a, b = ctypes.c_float(), ctypes.c_float()
+    rc = int(load().dynamix_timing_read(int(index), ctypes.byref(a), ctypes.byref(b)))
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+    return a.value, b.value
+
+
+def call_raw(grad_ptrs, batch_sizes, K, P, dtype, segment_offsets, num_segments, out_agg_ptr,
+             out_stats_ptr, stream_ptr, explicit_count=True):
+    """The C entry points on plain integers/sequences; returns the status.  grad_ptrs and
+    batch_sizes may be None to pass NULL.  Used directly by the error-path tests."""
+    lib = load()
+    ptrs = None if grad_ptrs is None else (ctypes.c_void_p * len(grad_ptrs))(*grad_ptrs)
+    b = None if batch_sizes is None else (ctypes.c_int32 * len(batch_sizes))(*batch_sizes)
+    off = None
+    if segment_offsets is not None:
+        off = (ctypes.c_int64 * len(segment_offsets))(*segment_offsets)
+    if explicit_count:
+        return int(lib.dynamix_grad_aggregate_stats_ex(
+            ptrs, b, K, P, dtype, off, num_segments, out_agg_ptr, out_stats_ptr, stream_ptr))
+    return int(lib.dynamix_grad_aggregate_stats(
+        ptrs, b, K, P, dtype, off, out_agg_ptr, out_stats_ptr, stream_ptr))
+
+
+def _marshal(grads, batch_sizes, segment_offsets, out_agg, out_stats, stream, stats_only):
+    import torch
+    K = len(grads)
+    g0 = grads[0]
+    if g0.dtype == torch.float32:
+        dtype = DYNAMIX_F32
+    elif g0.dtype == torch.bfloat16:
+        dtype = DYNAMIX_BF16
+    else:
+        raise TypeError("gradients must be float32 or bfloat16")
+    P = g0.numel()
+    for g in grads:
+        if not (g.is_cuda and g.is_contiguous() and g.dim() == 1 and g.numel() == P
+                and g.dtype == g0.dtype and g.device == g0.device):
+            raise ValueError("every gradient must be a contiguous 1-d device tensor of equal "
+                             "length, dtype and device")
+    S = 0 if segment_offsets is None else len(segment_offsets) - 1
+    if out_agg is None and not stats_only:
+        out_agg = torch.empty(P, dtype=torch.float32, device=g0.device)
+    if out_stats is None:
+        out_stats = torch.empty((1 + S, DYNAMIX_STATS_HEAD + 2 * K), dtype=torch.float64,
+                                device=g0.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(g0.device)
+    off = None if segment_offsets is None else [int(x) for x in segment_offsets]
+    return dict(grad_ptrs=[g.data_ptr() for g in grads], batch_sizes=[int(x) for x in batch_sizes],
+                K=K, P=P, dtype=dtype, segment_offsets=off, num_segments=S,
+                out_agg_ptr=None if out_agg is None else out_agg.data_ptr(),
+                out_stats_ptr=out_stats.data_ptr(), stream_ptr=stream.cuda_stream), out_agg, out_stats
+
+
+def dynamix_grad_aggregate_stats_ex(grads, batch_sizes, segment_offsets=None, out_agg=None,
+                                    out_stats=None, stream=None, stats_only=False):
+    """Enqueue one aggregate + statistics pass on `stream` (default: torch's current stream).
+
+    grads: K contiguous 1-d device tensors (float32 or bfloat16).  Returns (out_agg, out_stats):
+    float32[P] (None when stats_only) and float64[1+S, 8+2K]; valid after the stream is
+    synchronised.  Raises DynamixError on a non-zero status.
+    """
+    kw, out_agg, out_stats = _marshal(grads, batch_sizes, segment_offsets, out_agg, out_stats,
+                                      stream, stats_only)
+    rc = call_raw(explicit_count=True, **kw)
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+    return out_agg, out_stats
+
+
+def dynamix_grad_aggregate_stats(grads, batch_sizes, segment_offsets=None, out_agg=None,
+                                 out_stats=None, stream=None, stats_only=False):
+    """As dynamix_grad_aggregate_stats_ex, through the entry point that finds the number of
+    segments from the offsets array (it ends at the entry equal to P)."""
+    kw, out_agg, out_stats = _marshal(grads, batch_sizes, segment_offsets, out_agg, out_stats,
+                                      stream, stats_only)
+    rc = call_raw(explicit_count=False, **kw)
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+    return out_agg, out_stats

@@ -1,0 +1,453 @@
+// C ABI of libdynamix: argument validation, the cached launch plan and the two launches.
+// Everything before "plan" runs without touching HIP, so a bad call costs nothing on the device.
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <memory>
+#include <mutex>
+#include <vector>
+
+#include "../../include/dynamix.h"
+#include "dynamix_internal.h"
+
+namespace dynamix {
+
+#define DYNAMIX_UNIT_ENTRY(DT, LO) {launch_stream_pass_##DT##_##LO, occupancy_stream_pass_##DT##_##LO},
+struct Unit {
+    hipError_t (*launch)(int, int, const StreamArgs&, hipStream_t);
+    int (*occupancy)(int);
+};
+static const Unit kUnits[2][kKMax / 8] = {
+    {DYNAMIX_UNIT_ENTRY(0, 1) DYNAMIX_UNIT_ENTRY(0, 9) DYNAMIX_UNIT_ENTRY(0, 17)
+         DYNAMIX_UNIT_ENTRY(0, 25) DYNAMIX_UNIT_ENTRY(0, 33) DYNAMIX_UNIT_ENTRY(0, 41)
+             DYNAMIX_UNIT_ENTRY(0, 49) DYNAMIX_UNIT_ENTRY(0, 57)},
+    {DYNAMIX_UNIT_ENTRY(1, 1) DYNAMIX_UNIT_ENTRY(1, 9) DYNAMIX_UNIT_ENTRY(1, 17)
+         DYNAMIX_UNIT_ENTRY(1, 25) DYNAMIX_UNIT_ENTRY(1, 33) DYNAMIX_UNIT_ENTRY(1, 41)
+             DYNAMIX_UNIT_ENTRY(1, 49) DYNAMIX_UNIT_ENTRY(1, 57)}};
+
+hipError_t launch_stream_pass(int K, int dtype, int grid, const StreamArgs& a, hipStream_t s)
+{
+    if (K < 1 || K > kKMax || (dtype != kF32 && dtype != kBF16)) return hipErrorInvalidValue;
+    return kUnits[dtype][(K - 1) / 8].launch(K, grid, a, s);
+}
+
+int stream_pass_blocks_per_cu(int K, int dtype)
+{
+    if (K < 1 || K > kKMax || (dtype != kF32 && dtype != kBF16)) return 0;
+    return kUnits[dtype][(K - 1) / 8].occupancy(K);
+}
+
+namespace {
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// The launch plan of one (device, stream, K, dtype, P, segments): how the vector range is dealt
+// to blocks and cut at segment boundaries, plus the device workspace for the partial sums.
+struct Plan {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    int K = 0, dtype = 0;
+    int64_t P = 0;
+    std::vector<int64_t> offsets;  // empty without segments
+    int grid = 0, pieces = 0, records = 0;
+    bool uploaded = false;
+    std::vector<char> host;        // staging image of the tables
+    size_t table_bytes = 0;
+    char* blob = nullptr;          // device: tables followed by the partial sums
+    const Piece* d_pieces = nullptr;
+    const int32_t* d_block_first = nullptr;
+    const int32_t* d_rec_range = nullptr;
+    const double* d_rec_count = nullptr;
+    double* d_partials = nullptr;
+    uint64_t last_use = 0;
+    ~Plan()
+    {
+        if (blob) (void)hipFree(blob);
+    }
+};
+
+std::mutex g_mutex;
+std::vector<std::unique_ptr<Plan>> g_plans;
+uint64_t g_clock = 0;
+constexpr size_t kMaxPlans = 128;
+
+// Optional kernel timing: event triples (before the streaming pass, between the two kernels,
+// after the final reduction) recorded on the call's stream, one triple per call.
+struct Timing {
+    std::vector<hipEvent_t> events;  // 3 per slot
+    int capacity = 0;
+    int used = 0;
+};
+Timing g_timing;
+
+int env_int(const char* name, int fallback)
+{
+    const char* v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : fallback;
+}
+
+// The work decomposition (pure host arithmetic, no HIP): pieces in block order, the first piece
+// of every block, and per record its piece range and element count.
+struct Layout {
+    int grid = 0;
+    std::vector<Piece> pieces;
+    std::vector<int32_t> block_first, rec_range;
+    std::vector<double> rec_count;
+};
+
+void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int64_t max_grid,
+                 bool interleave, Layout& L)
+{
+    const int VEC = dtype == kF32 ? 4 : 8;
+    const int64_t tile = (int64_t)kBlock * unroll_for(K);  // vectors per block iteration
+    const int64_t nvec = ceil_div(P, VEC);
+    const int64_t ntiles = ceil_div(nvec, tile);
+    if (max_grid < 1) max_grid = 1;
+
+    if (interleave && S == 0) {
+        // block b takes tiles b, b + grid, b + 2 grid, ...
+        L.grid = (int)std::min<int64_t>(max_grid, ntiles);
+        for (int b = 0; b < L.grid; ++b) {
+            L.pieces.push_back(Piece{b * tile, nvec, L.grid * tile, 0, P, b});
+            L.block_first.push_back(b);
+        }
+        L.block_first.push_back(L.grid);
+    } else {
+        // every block owns one contiguous span of whole tiles; an odd tile count per span keeps
+        // neighbouring blocks from starting on the same memory channel phase
+        int64_t tiles_per_block = ceil_div(ntiles, max_grid);
+        if (tiles_per_block > 1) tiles_per_block |= 1;
+        const int64_t span = tiles_per_block * tile;
+        L.grid = (int)ceil_div(nvec, span);
+        std::vector<int32_t> per_block(L.grid, 0);
+        const int nseg = S > 0 ? S : 1;
+        for (int j = 0; j < nseg; ++j) {
+            const int64_t lo = S > 0 ? offsets[j] : 0, hi = S > 0 ? offsets[j + 1] : P;
+            const int64_t v_lo = lo / VEC, v_hi = ceil_div(hi, VEC);
+            for (int64_t b = v_lo / span; b <= (v_hi - 1) / span; ++b) {
+                Piece pc;
+                pc.v_begin = std::max(v_lo, b * span);
+                pc.v_end = std::min(v_hi, (b + 1) * span);
+                pc.v_step = tile;
+                pc.e_lo = std::max(lo, pc.v_begin * VEC);
+                pc.e_hi = std::min(hi, pc.v_end * VEC);
+                pc.block = b;
+                L.pieces.push_back(pc);
+                per_block[b] += 1;
+            }
+        }
+        int32_t acc = 0;
+        for (int b = 0; b < L.grid; ++b) {
+            L.block_first.push_back(acc);
+            acc += per_block[b];
+        }
+        L.block_first.push_back(acc);
+    }
+
+    // record 0 folds every piece; record 1 + j the pieces of segment j (consecutive by construction)
+    L.rec_range.push_back(0);
+    L.rec_range.push_back((int32_t)L.pieces.size());
+    L.rec_count.push_back((double)P);
+    int32_t first = 0;
+    size_t i = 0;
+    for (int j = 0; j < S; ++j) {
+        while (i < L.pieces.size() && L.pieces[i].e_lo < offsets[j + 1]) ++i;
+        L.rec_range.push_back(first);
+        L.rec_range.push_back((int32_t)i);
+        L.rec_count.push_back((double)(offsets[j + 1] - offsets[j]));
+        first = (int32_t)i;
+    }
+}
+
+int build_plan(Plan& pl, int S, const int64_t* offsets)
+{
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, pl.device) != hipSuccess) return DYNAMIX_ERR_HIP;
+    int per_cu = env_int("DYNAMIX_BLOCKS_PER_CU", 0);
+    if (per_cu <= 0) per_cu = stream_pass_blocks_per_cu(pl.K, pl.dtype);
+    if (per_cu <= 0) return DYNAMIX_ERR_HIP;
+
+    Layout L;
+    make_layout(pl.K, pl.dtype, pl.P, S, offsets, (int64_t)prop.multiProcessorCount * per_cu,
+                env_int("DYNAMIX_INTERLEAVE", 0) != 0, L);
+    pl.grid = L.grid;
+    pl.pieces = (int)L.pieces.size();
+    pl.records = 1 + S;
+
+    const int W = 2 * pl.K + 1;
+    const size_t o_pieces = 0;
+    const size_t o_block = align_up(o_pieces + L.pieces.size() * sizeof(Piece), 256);
+    const size_t o_range = align_up(o_block + L.block_first.size() * sizeof(int32_t), 256);
+    const size_t o_count = align_up(o_range + L.rec_range.size() * sizeof(int32_t), 256);
+    const size_t o_part = align_up(o_count + L.rec_count.size() * sizeof(double), 256);
+    const size_t total = o_part + (size_t)pl.pieces * W * sizeof(double);
+    pl.table_bytes = o_part;
+    pl.host.assign(o_part, 0);
+    std::memcpy(pl.host.data() + o_pieces, L.pieces.data(), L.pieces.size() * sizeof(Piece));
+    std::memcpy(pl.host.data() + o_block, L.block_first.data(), L.block_first.size() * sizeof(int32_t));
+    std::memcpy(pl.host.data() + o_range, L.rec_range.data(), L.rec_range.size() * sizeof(int32_t));
+    std::memcpy(pl.host.data() + o_count, L.rec_count.data(), L.rec_count.size() * sizeof(double));
+
+    void* dev = nullptr;
+    if (hipMalloc(&dev, total) != hipSuccess) {
+        (void)hipGetLastError();
+        return DYNAMIX_ERR_NOMEM;
+    }
+    pl.blob = static_cast<char*>(dev);
+    pl.d_pieces = reinterpret_cast<const Piece*>(pl.blob + o_pieces);
+    pl.d_block_first = reinterpret_cast<const int32_t*>(pl.blob + o_block);
+    pl.d_rec_range = reinterpret_cast<const int32_t*>(pl.blob + o_range);
+    pl.d_rec_count = reinterpret_cast<const double*>(pl.blob + o_count);
+    pl.d_partials = reinterpret_cast<double*>(pl.blob + o_part);
+    return DYNAMIX_OK;
+}
+
+// Finds or builds the plan; the caller holds g_mutex.
+int get_plan(int device, hipStream_t stream, int K, int dtype, int64_t P, int S,
+             const int64_t* offsets, Plan** out)
+{
+    for (auto& up : g_plans) {
+        Plan& pl = *up;
+        if (pl.device == device && pl.stream == stream && pl.K == K && pl.dtype == dtype &&
+            pl.P == P && (int)pl.offsets.size() == (S > 0 ? S + 1 : 0) &&
+            (S == 0 || std::memcmp(pl.offsets.data(), offsets, sizeof(int64_t) * (S + 1)) == 0)) {
+            pl.last_use = ++g_clock;
+            *out = &pl;
+            return DYNAMIX_OK;
+        }
+    }
+    if (g_plans.size() >= kMaxPlans) {
+        // drop the least recently used plan; hipFree waits for work that may still read it
+        auto it = std::min_element(g_plans.begin(), g_plans.end(),
+                                   [](const auto& x, const auto& y) { return x->last_use < y->last_use; });
+        g_plans.erase(it);
+    }
+    auto up = std::make_unique<Plan>();
+    up->device = device;
+    up->stream = stream;
+    up->K = K;
+    up->dtype = dtype;
+    up->P = P;
+    if (S > 0) up->offsets.assign(offsets, offsets + S + 1);
+    const int rc = build_plan(*up, S, offsets);
+    if (rc != DYNAMIX_OK) return rc;
+    up->last_use = ++g_clock;
+    *out = up.get();
+    g_plans.push_back(std::move(up));
+    return DYNAMIX_OK;
+}
+
+int check_shape(int32_t K, int64_t P, int32_t dtype, const int64_t* offsets, int64_t S)
+{
+    if (K < 1 || K > kKMax || P < 1 || (dtype != DYNAMIX_F32 && dtype != DYNAMIX_BF16))
+        return DYNAMIX_ERR_ARG;
+    if (S < 0 || S > INT32_MAX / 4) return DYNAMIX_ERR_SEGMENTS;
+    if ((S == 0) != (offsets == nullptr)) return DYNAMIX_ERR_SEGMENTS;
+    if (S > 0) {
+        if (offsets[0] != 0 || offsets[S] != P) return DYNAMIX_ERR_SEGMENTS;
+        for (int64_t j = 0; j < S; ++j)
+            if (offsets[j + 1] <= offsets[j]) return DYNAMIX_ERR_SEGMENTS;
+    }
+    return DYNAMIX_OK;
+}
+
+int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t P, int32_t dtype,
+        const int64_t* offsets, int64_t S, float* out_agg, double* out_stats, void* stream_v)
+{
+    // ---- validation: no HIP call before this block has passed
+    if (!grads || !batch_sizes || !out_stats) return DYNAMIX_ERR_NULL;
+    int vrc = check_shape(K, P, dtype, offsets, S);
+    if (vrc != DYNAMIX_OK) return vrc;
+    for (int k = 0; k < K; ++k) {
+        if (!grads[k]) return DYNAMIX_ERR_NULL;
+        if (batch_sizes[k] <= 0) return DYNAMIX_ERR_ARG;
+    }
+    for (int k = 0; k < K; ++k)
+        if (reinterpret_cast<uintptr_t>(grads[k]) & 15u) return DYNAMIX_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(out_agg) & 15u) || (reinterpret_cast<uintptr_t>(out_stats) & 7u))
+        return DYNAMIX_ERR_ALIGN;
+
+    // ---- weights: B in 64-bit integers, w_k = b_k / B rounded once to fp32
+    int64_t B = 0;
+    for (int k = 0; k < K; ++k) B += batch_sizes[k];
+
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return DYNAMIX_ERR_HIP;
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    Plan* pl = nullptr;
+    const int rc = get_plan(device, stream, K, dtype, P, (int)S, offsets, &pl);
+    if (rc != DYNAMIX_OK) return rc;
+    if (!pl->uploaded) {
+        if (hipMemcpyAsync(pl->blob, pl->host.data(), pl->table_bytes, hipMemcpyHostToDevice,
+                           stream) != hipSuccess)
+            return DYNAMIX_ERR_HIP;
+        pl->uploaded = true;
+    }
+
+    StreamArgs sa;
+    std::memset(&sa, 0, sizeof sa);
+    FinalArgs fa;
+    std::memset(&fa, 0, sizeof fa);
+    for (int k = 0; k < K; ++k) {
+        sa.g[k] = grads[k];
+        sa.w[k] = (float)((double)batch_sizes[k] / (double)B);
+        fa.b[k] = (double)batch_sizes[k];
+    }
+    sa.pieces = pl->d_pieces;
+    sa.block_first = pl->d_block_first;
+    sa.out_agg = out_agg;
+    sa.partials = pl->d_partials;
+    fa.B = (double)B;
+    fa.partials = pl->d_partials;
+    fa.rec_range = pl->d_rec_range;
+    fa.rec_count = pl->d_rec_count;
+    fa.out_stats = out_stats;
+    fa.K = K;
+
+    hipEvent_t* ev = nullptr;
+    if (g_timing.used < g_timing.capacity) ev = &g_timing.events[3 * (size_t)g_timing.used++];
+    if (ev && hipEventRecord(ev[0], stream) != hipSuccess) return DYNAMIX_ERR_HIP;
+    if (launch_stream_pass(K, dtype, pl->grid, sa, stream) != hipSuccess) return DYNAMIX_ERR_HIP;
+    if (ev && hipEventRecord(ev[1], stream) != hipSuccess) return DYNAMIX_ERR_HIP;
+    if (launch_final_reduce(pl->records, fa, stream) != hipSuccess) return DYNAMIX_ERR_HIP;
+    if (ev && hipEventRecord(ev[2], stream) != hipSuccess) return DYNAMIX_ERR_HIP;
+    return DYNAMIX_OK;
+}
+
+}  // namespace
+}  // namespace dynamix
+
+extern "C" {
+
+int dynamix_grad_aggregate_stats_ex(const void* const* grads, const int32_t* batch_sizes,
+                                    int32_t K, int64_t P, int32_t dtype,
+                                    const int64_t* segment_offsets, int64_t num_segments,
+                                    float* out_agg, double* out_stats, void* stream)
+{
+    try {
+        return dynamix::run(grads, batch_sizes, K, P, dtype, segment_offsets, num_segments, out_agg,
+                            out_stats, stream);
+    } catch (const std::bad_alloc&) {
+        return DYNAMIX_ERR_NOMEM;
+    } catch (...) {
+        return DYNAMIX_ERR_HIP;
+    }
+}
+
+int dynamix_grad_aggregate_stats(const void* const* grads, const int32_t* batch_sizes, int32_t K,
+                                 int64_t P, int32_t dtype, const int64_t* segment_offsets,
+                                 float* out_agg, double* out_stats, void* stream)
+{
+    int64_t S = 0;
+    if (segment_offsets) {
+        // the array ends at the first entry equal to P; entries must rise strictly towards it
+        if (P < 1) return DYNAMIX_ERR_ARG;
+        if (segment_offsets[0] != 0) return DYNAMIX_ERR_SEGMENTS;
+        while (segment_offsets[S] < P) {
+            if (segment_offsets[S + 1] <= segment_offsets[S]) return DYNAMIX_ERR_SEGMENTS;
+            ++S;
+        }
+        if (segment_offsets[S] != P || S == 0) return DYNAMIX_ERR_SEGMENTS;
+    }
+    return dynamix_grad_aggregate_stats_ex(grads, batch_sizes, K, P, dtype, segment_offsets, S,
+                                           out_agg, out_stats, stream);
+}
+
+int64_t dynamix_stats_count(int32_t K, int64_t num_segments)
+{
+    if (K < 1 || K > DYNAMIX_K_MAX || num_segments < 0) return -1;
+    return (1 + num_segments) * (int64_t)(DYNAMIX_STATS_HEAD + 2 * K);
+}
+
+const char* dynamix_status_string(int status)
+{
+    switch (status) {
+    case DYNAMIX_OK: return "ok";
+    case DYNAMIX_ERR_NULL: return "a required pointer is NULL";
+    case DYNAMIX_ERR_ARG: return "invalid K, P, dtype or batch size";
+    case DYNAMIX_ERR_SEGMENTS: return "invalid segment offsets";
+    case DYNAMIX_ERR_ALIGN: return "misaligned pointer";
+    case DYNAMIX_ERR_NOMEM: return "workspace allocation failed";
+    case DYNAMIX_ERR_HIP: return "HIP runtime call failed";
+    default: return "unknown status";
+    }
+}
+
+int64_t dynamix_plan_describe(int32_t K, int64_t P, int32_t dtype, const int64_t* segment_offsets,
+                              int64_t num_segments, int64_t max_blocks, int32_t interleave,
+                              int64_t* pieces_out, int64_t capacity)
+{
+    const int rc = dynamix::check_shape(K, P, dtype, segment_offsets, num_segments);
+    if (rc != DYNAMIX_OK) return -rc;
+    if (max_blocks < 1 || capacity < 0 || (capacity > 0 && !pieces_out)) return -DYNAMIX_ERR_ARG;
+    try {
+        dynamix::Layout L;
+        dynamix::make_layout(K, dtype, P, (int)num_segments, segment_offsets, max_blocks,
+                             interleave != 0, L);
+        const int64_t n = (int64_t)L.pieces.size();
+        for (int64_t i = 0; i < n && i < capacity; ++i) {
+            const dynamix::Piece& pc = L.pieces[i];
+            int64_t* o = pieces_out + 6 * i;
+            o[0] = pc.v_begin; o[1] = pc.v_end; o[2] = pc.v_step;
+            o[3] = pc.e_lo; o[4] = pc.e_hi; o[5] = pc.block;
+        }
+        return n;
+    } catch (...) {
+        return -DYNAMIX_ERR_NOMEM;
+    }
+}
+
+int dynamix_timing_begin(int32_t capacity)
+{
+    if (capacity < 0 || capacity > (1 << 20)) return DYNAMIX_ERR_ARG;
+    std::lock_guard<std::mutex> lock(dynamix::g_mutex);
+    dynamix::Timing& t = dynamix::g_timing;
+    for (hipEvent_t e : t.events) (void)hipEventDestroy(e);
+    t.events.clear();
+    t.capacity = t.used = 0;
+    try {
+        t.events.reserve(3 * (size_t)capacity);
+    } catch (...) {
+        return DYNAMIX_ERR_NOMEM;
+    }
+    for (int i = 0; i < 3 * capacity; ++i) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return DYNAMIX_ERR_HIP;
+        t.events.push_back(e);
+    }
+    t.capacity = capacity;
+    return DYNAMIX_OK;
+}
+
+int32_t dynamix_timing_count(void)
+{
+    std::lock_guard<std::mutex> lock(dynamix::g_mutex);
+    return dynamix::g_timing.used;
+}
+
+int dynamix_timing_read(int32_t index, float* stream_pass_ms, float* final_reduce_ms)
+{
+    if (!stream_pass_ms || !final_reduce_ms) return DYNAMIX_ERR_NULL;
+    std::lock_guard<std::mutex> lock(dynamix::g_mutex);
+    dynamix::Timing& t = dynamix::g_timing;
+    if (index < 0 || index >= t.used) return DYNAMIX_ERR_ARG;
+    hipEvent_t* ev = &t.events[3 * (size_t)index];
+    if (hipEventElapsedTime(stream_pass_ms, ev[0], ev[1]) != hipSuccess ||
+        hipEventElapsedTime(final_reduce_ms, ev[1], ev[2]) != hipSuccess) {
+        (void)hipGetLastError();
+        return DYNAMIX_ERR_HIP;
+    }
+    return DYNAMIX_OK;
+}
+
+int dynamix_release_cached(void)
+{
+    std::lock_guard<std::mutex> lock(dynamix::g_mutex);
+    dynamix::g_plans.clear();
+    return DYNAMIX_OK;
+}
+
+}  // extern "C"

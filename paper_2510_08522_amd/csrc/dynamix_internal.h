@@ -1,0 +1,66 @@
+// Internal declarations shared by the HIP translation units of libdynamix (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dynamix {
+
+constexpr int kKMax = 64;        // workers per call; pointers and weights travel by value
+constexpr int kBlock = 256;      // threads per block of the streaming pass: 4 wave64
+constexpr int kWaves = kBlock / 64;
+constexpr int kHead = 8;         // scalars in front of the per-worker entries of a record
+
+enum : int { kF32 = 0, kBF16 = 1 };
+
+// Vectors (16-byte loads) per thread and block iteration.  Small K gets several so that each
+// lane keeps enough independent loads in flight; K x U x 4 data registers stay live until the
+// aggregate of the vector is known.
+constexpr int unroll_for(int K) { return K <= 2 ? 8 : K <= 8 ? 4 : K <= 16 ? 2 : 1; }
+
+// One unit of streaming work: 16-byte vectors v_begin, v_begin + v_step, ... below v_end are the
+// starts of the block iterations; elements outside [e_lo, e_hi) are masked (segment edges and
+// the ragged tail).  One partial record of 2K+1 sums is produced per piece.
+struct Piece {
+    int64_t v_begin;
+    int64_t v_end;
+    int64_t v_step;
+    int64_t e_lo;
+    int64_t e_hi;
+    int64_t block;   // owning block (diagnostics only)
+};
+
+struct StreamArgs {
+    const void* g[kKMax];        // K device pointers
+    float w[kKMax];              // b_k / B, rounded once to fp32
+    const Piece* pieces;
+    const int32_t* block_first;  // [grid + 1] first piece of each block
+    float* out_agg;              // may be null
+    double* partials;            // [pieces][2K+1]: A, n_0..n_{K-1}, d_0..d_{K-1}
+};
+
+struct FinalArgs {
+    double b[kKMax];             // batch sizes
+    double B;                    // their sum
+    const double* partials;
+    const int32_t* rec_range;    // [records][2]: first and one-past-last piece of each record
+    const double* rec_count;     // [records] elements covered
+    double* out_stats;           // [records][8 + 2K]
+    int32_t K;
+};
+
+// Enqueue the streaming pass for (K, dtype); returns hipErrorInvalidValue for an unknown pair.
+hipError_t launch_stream_pass(int K, int dtype, int grid, const StreamArgs& a, hipStream_t s);
+// Resident blocks per compute unit of that kernel (0 on error).
+int stream_pass_blocks_per_cu(int K, int dtype);
+hipError_t launch_final_reduce(int records, const FinalArgs& a, hipStream_t s);
+
+// One instantiation unit per dtype and group of eight K: launch_stream_pass_<dtype>_<first K>.
+#define DYNAMIX_DECLARE_UNIT(DT, LO)                                                        \
+    hipError_t launch_stream_pass_##DT##_##LO(int K, int grid, const StreamArgs& a, hipStream_t s); \
+    int occupancy_stream_pass_##DT##_##LO(int K);
+#define DYNAMIX_FOR_EACH_UNIT(X) \
+    X(0, 1) X(0, 9) X(0, 17) X(0, 25) X(0, 33) X(0, 41) X(0, 49) X(0, 57) \
+    X(1, 1) X(1, 9) X(1, 17) X(1, 25) X(1, 33) X(1, 41) X(1, 49) X(1, 57)
+DYNAMIX_FOR_EACH_UNIT(DYNAMIX_DECLARE_UNIT)
+
+}  // namespace dynamix

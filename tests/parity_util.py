@@ -1,0 +1,84 @@
+"""Comparison of the HIP path's outputs with the CPU oracle's, to the stated tolerances.
+
+Tolerances (relative): 1e-5 for the aggregate vector and the squared norms with fp32 inputs,
+1e-3 with bf16 inputs, 1e-4 for the noise scale (1e-3 with bf16 inputs).
+
+A vector is compared in the 2-norm and in the max-norm relative to the oracle's largest entry,
+because single entries of a weighted mean can cancel to almost nothing.
+
+The sums A, n_k, d_k, T of a record meet the plain relative tolerance whenever the record is
+well conditioned: it covers at least 4096 elements (no single cancelling entry can dominate) and
+the workers are not identical to within rounding (d_k >= 1e-6 max(n_k, A)).  Otherwise the bound
+adds what the fp32 evaluation of G_i = sum_k w_k g_ki (K fused multiply-adds with weights rounded
+once) can contribute: |dG_i| <= eps_c sqrt(sum_k w_k g_ki^2) with eps_c = K 2^-23, hence
+|dA| <= 2 eps_c sqrt(A N) + eps_c^2 N with N = sum_k w_k n_k, and
+|dd_k| <= 2 eps_c sqrt(d_k M) + eps_c^2 M with M = max(n_k, A).  Ratios inherit the relative
+bounds of their parts; A - T/B is compared against the size of its two parts.
+"""
+import numpy as np
+
+HEAD = 8
+
+
+def tolerances(is_bf16):
+    return (1e-3, 1e-3) if is_bf16 else (1e-5, 1e-4)
+
+
+def compare(agg_gpu, stats_gpu, agg_ref, stats_ref, batch_sizes, is_bf16=False, where=""):
+    tol, tol_ns = tolerances(is_bf16)
+    K = len(batch_sizes)
+    B = float(np.sum(batch_sizes))
+    stats_gpu = np.asarray(stats_gpu, dtype=np.float64)
+    assert stats_gpu.shape == stats_ref.shape, where
+    if agg_gpu is not None:
+        a = np.asarray(agg_gpu, dtype=np.float64)
+        assert a.shape == agg_ref.shape
+        den = float(np.linalg.norm(agg_ref))
+        diff = a - agg_ref
+        if den > 0:
+            assert np.linalg.norm(diff) <= tol * den, (where, "agg 2-norm", np.linalg.norm(diff) / den)
+            assert np.abs(diff).max() <= tol * np.abs(agg_ref).max(), (where, "agg max-norm")
+        else:
+            assert not diff.any()
+    for r in range(stats_ref.shape[0]):
+        g, o = stats_gpu[r], stats_ref[r]
+        tag = "%s record %d" % (where, r)
+        A, T = o[0], o[1]
+        n, d = o[HEAD:HEAD + K], o[HEAD + K:HEAD + 2 * K]
+        assert g[7] == o[7], tag
+        if not np.isfinite(o[:7]).all() or not np.isfinite(o[HEAD:]).all():
+            # degenerate record (e.g. all-zero gradients): same non-finite pattern, same finite values
+            assert (np.isnan(g) == np.isnan(o)).all(), tag
+            fin = np.isfinite(o)
+            np.testing.assert_allclose(g[fin], o[fin], rtol=tol_ns, atol=0, err_msg=tag)
+            continue
+        w = np.asarray(batch_sizes, dtype=np.float64) / B
+        eps_c = K * 2.0 ** -23
+        big = o[7] >= 4096
+        N = float(np.dot(w, n))
+        bound_A = tol * A + (0.0 if big else 2 * eps_c * np.sqrt(A * N) + eps_c ** 2 * N)
+        assert abs(g[0] - A) <= bound_A, (tag, "A", g[0], A)
+        gn, gd = g[HEAD:HEAD + K], g[HEAD + K:HEAD + 2 * K]
+        assert (np.abs(gn - n) <= tol * n).all(), (tag, "n_k")
+        M = np.maximum(n, A)
+        well = big & (d >= 1e-6 * M)
+        bound_d = tol * d + np.where(well, 0.0, 2 * eps_c * np.sqrt(d * M) + eps_c ** 2 * M)
+        assert (np.abs(gd - d) <= bound_d).all(), (tag, "d_k", gd, d)
+        bound_T = float(np.dot(batch_sizes, bound_d)) / max(K - 1, 1)
+        assert abs(g[1] - T) <= bound_T, (tag, "T", g[1], T)
+        part = abs(A) + abs(T) / B
+        bound_U = bound_A + bound_T / B
+        assert abs(g[2] - o[2]) <= bound_U + tol * part, (tag, "A_unb", g[2], o[2])
+        if K > 1:
+            # the ratios are checked where they mean something: T is not a rounding residue,
+            # and for the unbiased noise scale A - T/B has not cancelled
+            if T > 1e-6 * B * A and A > 0:
+                slack = (bound_A - tol * A) / A + (bound_T - tol * T) / T
+                assert abs(g[4] - o[4]) <= (tol_ns + slack) * abs(o[4]), (tag, "noise_scale_biased", g[4], o[4])
+                assert abs(g[5] - o[5]) <= (tol_ns + slack) * abs(o[5]), (tag, "sigma2_norm")
+                assert abs(g[6] - o[6]) <= (tol_ns + slack) * abs(o[6]), (tag, "sigma_norm")
+                if abs(o[2]) > 0.05 * part:
+                    slack_u = (bound_U - tol * part) / abs(o[2]) + (bound_T - tol * T) / T
+                    assert abs(g[3] - o[3]) <= (tol_ns + slack_u) * abs(o[3]), (tag, "noise_scale", g[3], o[3])
+        else:
+            assert g[1] == 0.0 and g[3] == 0.0 and g[4] == 0.0 and g[6] == 0.0, tag

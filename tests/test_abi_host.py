@@ -1,0 +1,148 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads and exports what the header
+declares, argument validation happens before any HIP call, and the work decomposition covers
+every element exactly once."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2510_08522_amd as D
+from paper_2510_08522_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dynamix.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dynamix_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"dynamix_grad_aggregate_stats", "dynamix_grad_aggregate_stats_ex",
+            "dynamix_stats_count", "dynamix_status_string", "dynamix_release_cached",
+            "dynamix_plan_describe"} <= set(names)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    # the Python layer carries the same names
+    for n in names:
+        assert hasattr(D, n), n
+
+
+def test_stats_count_and_status_strings():
+    assert D.dynamix_stats_count(4, 0) == 16
+    assert D.dynamix_stats_count(32, 148) == 149 * 72
+    assert D.dynamix_stats_count(0, 0) == -1 and D.dynamix_stats_count(65, 0) == -1
+    assert D.dynamix_stats_count(4, -1) == -1
+    seen = {D.dynamix_status_string(i) for i in range(7)}
+    assert len(seen) == 7 and D.dynamix_status_string(0) == "ok"
+    assert D.dynamix_status_string(99) == "unknown status"
+
+
+A16, ST = 0x1000, 0x2000     # fake, suitably aligned "device" addresses: never dereferenced
+
+
+def raw(ptrs, b, K, P, dtype=0, off=None, S=0, agg=A16, stats=ST, explicit=True):
+    return B.call_raw(ptrs, b, K, P, dtype, off, S, agg, stats, None, explicit_count=explicit)
+
+
+def test_validation_precedes_any_device_work():
+    ok_p, ok_b = [A16, A16 + 64], [32, 64]
+    assert raw(None, ok_b, 2, 100) == B.DYNAMIX_ERR_NULL
+    assert raw(ok_p, None, 2, 100) == B.DYNAMIX_ERR_NULL
+    assert raw(ok_p, ok_b, 2, 100, stats=None) == B.DYNAMIX_ERR_NULL
+    assert raw([A16, None], ok_b, 2, 100) == B.DYNAMIX_ERR_NULL
+    assert raw(ok_p, ok_b, 0, 100) == B.DYNAMIX_ERR_ARG
+    assert raw([A16] * 65, [1] * 65, 65, 100) == B.DYNAMIX_ERR_ARG
+    assert raw(ok_p, ok_b, 2, 0) == B.DYNAMIX_ERR_ARG
+    assert raw(ok_p, ok_b, 2, 100, dtype=2) == B.DYNAMIX_ERR_ARG
+    assert raw(ok_p, [32, 0], 2, 100) == B.DYNAMIX_ERR_ARG
+    assert raw(ok_p, [32, -5], 2, 100) == B.DYNAMIX_ERR_ARG
+    assert raw([A16, A16 + 4], ok_b, 2, 100) == B.DYNAMIX_ERR_ALIGN
+    assert raw(ok_p, ok_b, 2, 100, agg=A16 + 8) == B.DYNAMIX_ERR_ALIGN
+    assert raw(ok_p, ok_b, 2, 100, stats=ST + 4) == B.DYNAMIX_ERR_ALIGN
+
+
+def test_segment_offsets_validation():
+    p, b = [A16, A16 + 64], [32, 64]
+    bad = B.DYNAMIX_ERR_SEGMENTS
+    assert raw(p, b, 2, 100, off=[1, 50, 100], S=2) == bad          # does not start at 0
+    assert raw(p, b, 2, 100, off=[0, 50, 50, 100], S=3) == bad      # empty segment
+    assert raw(p, b, 2, 100, off=[0, 60, 50, 100], S=3) == bad      # decreasing
+    assert raw(p, b, 2, 100, off=[0, 50, 99], S=2) == bad           # does not end at P
+    assert raw(p, b, 2, 100, off=[0, 50, 100], S=0) == bad          # offsets without a count
+    assert raw(p, b, 2, 100, off=None, S=2) == bad                  # count without offsets
+    assert raw(p, b, 2, 100, off=[0, 50, 100], S=-1) == bad
+    # the entry point that scans for the terminating entry
+    assert raw(p, b, 2, 100, off=[0, 50, 120], explicit=False) == bad
+    assert raw(p, b, 2, 100, off=[0, 50, 50, 100], explicit=False) == bad
+    assert raw(p, b, 2, 100, off=[5, 50, 100], explicit=False) == bad
+    assert raw(p, b, 2, 0, off=[0, 50, 100], explicit=False) == B.DYNAMIX_ERR_ARG
+
+
+def unroll_for(K):
+    return 8 if K <= 2 else 4 if K <= 8 else 2 if K <= 16 else 1
+
+
+def check_cover(K, P, dtype, off, max_blocks, interleave=False):
+    """Replay the kernel's iteration space on the host and count how often each element is
+    touched by an unmasked lane, per record."""
+    vec = 4 if dtype == 0 else 8
+    tile = 256 * unroll_for(K)
+    pcs = D.dynamix_plan_describe(K, P, dtype, off, max_blocks, interleave)
+    assert len(pcs) >= 1
+    assert (np.diff(pcs[:, 5]) >= 0).all()                      # pieces sorted by owning block
+    assert pcs[:, 5].max() < max_blocks
+    assert set(pcs[:, 5].tolist()) == set(range(int(pcs[:, 5].max()) + 1))   # no idle block index
+    cover = np.zeros(P, dtype=np.int32)
+    for vb, ve, step, elo, ehi, _ in pcs.tolist():
+        assert 0 <= vb < ve and step >= tile and step % tile == 0
+        if interleave:      # every piece strides over the whole range, clipped to [0, P)
+            assert (elo, ehi) == (0, P) and ve * vec >= P
+        else:
+            assert vb * vec <= elo < ehi <= min(P, ve * vec)
+        for v0 in range(vb, ve, step):
+            lo, hi = max(elo, v0 * vec), min(ehi, (v0 + tile) * vec)
+            if lo < hi:
+                cover[lo:hi] += 1
+    assert (cover == 1).all()
+    if off is not None:                                          # pieces never straddle a segment
+        seg_of = np.searchsorted(np.asarray(off), pcs[:, 3], side="right") - 1
+        assert (np.asarray(off)[seg_of + 1] >= pcs[:, 4]).all()
+        assert (np.diff(seg_of) >= 0).all()
+    return pcs
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_plan_covers_every_element_once(dtype):
+    rng = np.random.default_rng(5)
+    for K, P, mb in [(1, 1, 512), (4, 3, 512), (4, 1_000_000, 512), (8, 1_000_003, 1024),
+                     (32, 777_777, 512), (64, 300_001, 256), (16, 2_000_001, 7), (3, 65_537, 1)]:
+        check_cover(K, P, dtype, None, mb)
+        check_cover(K, P, dtype, None, mb, interleave=True)
+        S = int(min(P, rng.integers(1, 40)))
+        cuts = np.sort(rng.choice(np.arange(1, P), size=S - 1, replace=False)) if S > 1 else []
+        off = [0] + [int(c) for c in cuts] + [P]
+        check_cover(K, P, dtype, off, mb)
+    # one-element segments and boundaries inside a single vector
+    check_cover(4, 5000, dtype, [0, 1, 2, 130, 131, 4099, 4100, 5000], 4)
+    check_cover(5, 20, dtype, list(range(21)), 512)
+
+
+def test_plan_for_the_headline_shape_is_balanced():
+    pcs = check_cover(32, 138_000_000, 0, None, 512)
+    vec_per_piece = pcs[:, 1] - pcs[:, 0]
+    assert len(pcs) <= 512
+    assert vec_per_piece.max() <= 1.01 * (138_000_000 / 4) / len(pcs) + 256
+    assert ((vec_per_piece[:-1] // 256) % 2 == 1).all()         # odd tile count per span
+
+
+def test_plan_describe_rejects_bad_shapes():
+    with pytest.raises(D.DynamixError):
+        D.dynamix_plan_describe(0, 10, 0)
+    with pytest.raises(D.DynamixError):
+        D.dynamix_plan_describe(4, 10, 0, [0, 5, 9])

@@ -1,0 +1,197 @@
+"""Parity of the HIP path with the CPU oracle on the same seeded inputs (needs an MI355X).
+
+Every call goes through the C ABI (ctypes binding); the oracle runs on the host copy of the very
+same tensors.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_08522_amd as D
+from paper_2510_08522_amd import workloads as W
+from parity_util import HEAD, compare
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+THREADS = 16
+
+
+def run_gpu(w, entry=None, **kw):
+    entry = entry or D.dynamix_grad_aggregate_stats_ex
+    agg, st = entry(w.grads, w.batch_sizes, w.segment_offsets, **kw)
+    torch.cuda.synchronize()
+    return (None if agg is None else agg.cpu().numpy()), st.cpu().numpy()
+
+
+def run_oracle(oracle_mod, w, want_agg=True):
+    return oracle_mod.aggregate_stats(w.host_arrays(), w.batch_sizes, w.segment_offsets,
+                                      want_agg=want_agg, threads=THREADS)
+
+
+def check(oracle_mod, w, where):
+    print("case", where, "K", w.K, "P", w.P, w.dtype, "S", w.S, flush=True)
+    agg, st = run_gpu(w)
+    ragg, rst = run_oracle(oracle_mod, w)
+    compare(agg, st, ragg, rst, w.batch_sizes, is_bf16=(w.dtype == torch.bfloat16), where=where)
+    return agg, st, ragg, rst
+
+
+# ------------------------------------------------------------------ the named configurations
+@pytest.mark.parametrize("name", ["C1", "C2", "C3"])
+def test_config_full_size(oracle_mod, name):
+    w = W.config(name, device=DEV)
+    _, st, _, _ = check(oracle_mod, w, name)
+    expected = 2000.0 if name == "C3" else 100.0
+    assert abs(st[0, D.STAT["noise_scale"]] / expected - 1.0) < 0.05
+
+
+def test_config_c4_full_size_headline(oracle_mod):
+    # K=32, P=138M fp32: the shape and launch configuration the benchmark times
+    w = W.config("C4", device=DEV)
+    _, st, _, _ = check(oracle_mod, w, "C4")
+    assert abs(st[0, D.STAT["noise_scale"]] / 100.0 - 1.0) < 0.02
+
+
+def test_config_c5_full_size_segments(oracle_mod):
+    w = W.config("C5", device=DEV)
+    assert w.S == 148
+    check(oracle_mod, w, "C5")
+
+
+# ------------------------------------------------------------------ shapes: every K, ragged tails
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 24, 31, 32, 33, 48, 63, 64])
+def test_worker_counts_and_ragged_tail(oracle_mod, K, dtype):
+    rng = np.random.default_rng(1000 + K)
+    # several tiles per block iteration plus a tail that is not a whole vector
+    P = int(rng.integers(60_000, 90_000)) * 4 + int(rng.integers(1, 4))
+    b = rng.integers(8, 1025, size=K)
+    w = W.make(K, P, dtype, b, 1e-3, 1e-2, seed=7 + K, device=DEV)
+    check(oracle_mod, w, "K=%d" % K)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("P", [1, 2, 3, 4, 5, 7, 8, 9, 255, 1023, 1024, 1025, 4097, 262_145])
+def test_tiny_and_boundary_lengths(oracle_mod, P, dtype):
+    w = W.make(3, P, dtype, [32, 57, 132], 1e-3, 1e-2, seed=P, device=DEV)
+    check(oracle_mod, w, "P=%d" % P)
+
+
+def test_all_64_workers_large(oracle_mod):
+    rng = np.random.default_rng(64)
+    w = W.make(64, 3_000_001, torch.float32, rng.integers(32, 1025, size=64), 1e-3, 1e-2,
+               seed=64, device=DEV)
+    check(oracle_mod, w, "K=64 large")
+
+
+# ------------------------------------------------------------------ segments
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_segments_at_odd_offsets(oracle_mod, dtype):
+    P = 1_200_007
+    off = [0, 1, 2, 3, 7, 8, 130, 131, 4099, 4100, 65_537, 262_143, 262_145, 700_001, P - 1, P]
+    rng = np.random.default_rng(3)
+    sig = np.exp(rng.uniform(np.log(1e-4), np.log(1e-1), size=len(off) - 1))
+    w = W.make(6, P, dtype, [16, 48, 100, 125, 256, 1024], 1e-3, sig, seed=11, device=DEV,
+               segment_offsets=off)
+    _, st, _, rst = check(oracle_mod, w, "odd segments")
+    assert st.shape == (len(off), HEAD + 12)
+    # the entry point that finds the number of segments itself gives the same bits
+    _, st2 = run_gpu(w, entry=D.dynamix_grad_aggregate_stats)
+    assert np.array_equal(st, st2)
+
+
+def test_many_one_element_segments(oracle_mod):
+    P = 3000
+    w = W.make(4, P, torch.float32, [32, 64, 96, 128], 1e-3, 1e-2, seed=5, device=DEV,
+               segment_offsets=list(range(P + 1)))
+    check(oracle_mod, w, "one-element segments")
+
+
+def test_c5_recipe_small(oracle_mod):
+    w = W.config("C5", device=DEV, P=2_000_003)
+    check(oracle_mod, w, "C5 small")
+
+
+# ------------------------------------------------------------------ special and degenerate inputs
+def test_single_worker_identity_is_bitwise(oracle_mod):
+    w = W.make(1, 100_003, torch.float32, [77], 1e-3, 1e-2, seed=1, device=DEV)
+    agg, st, _, _ = check(oracle_mod, w, "K=1")
+    assert np.array_equal(agg, w.grads[0].cpu().numpy())
+    assert st[0, 1] == 0.0 and st[0, HEAD + 1] == 0.0
+
+
+def test_identical_workers(oracle_mod):
+    w = W.make(1, 500_001, torch.float32, [64], 1e-3, 1e-2, seed=2, device=DEV)
+    w.grads = [w.grads[0], w.grads[0].clone(), w.grads[0].clone(), w.grads[0].clone()]
+    w.K, w.batch_sizes = 4, np.array([32, 32, 64, 128], dtype=np.int32)    # B = 256: exact weights
+    agg, st, _, _ = check(oracle_mod, w, "identical")
+    assert np.array_equal(agg, w.grads[0].cpu().numpy())
+    assert st[0, 1] == 0.0 and (st[0, HEAD + 4:] == 0.0).all()
+    w.batch_sizes = np.array([33, 50, 100, 77], dtype=np.int32)             # inexact weights
+    _, st, _, _ = check(oracle_mod, w, "identical, inexact weights")
+    assert st[0, 1] <= 1e-10 * st[0, 0] * w.batch_sizes.sum()
+
+
+def test_all_zero_gradients(oracle_mod):
+    w = W.make(3, 10_001, torch.float32, [32, 64, 96], 0.0, 0.0, seed=3, device=DEV)
+    agg, st, _, rst = check(oracle_mod, w, "zeros")
+    assert not agg.any() and np.isnan(st[0, 3]) and np.isnan(rst[0, 3])
+
+
+def test_wide_dynamic_range(oracle_mod):
+    w = W.make(5, 300_001, torch.float32, [8, 32, 100, 512, 1024], 1e-3, 1e-2, seed=4, device=DEV)
+    scale = torch.exp(torch.linspace(-20.0, 20.0, w.P, device=DEV))
+    w.grads = [(g * scale).contiguous() for g in w.grads]
+    check(oracle_mod, w, "dynamic range")
+
+
+def test_non_finite_inputs_propagate():
+    w = W.make(3, 50_000, torch.float32, [32, 64, 96], 1e-3, 1e-2, seed=6, device=DEV)
+    w.grads[1][12_345] = float("inf")
+    w.grads[2][40_000] = float("nan")
+    agg, st = run_gpu(w)
+    assert np.isinf(agg[12_345]) and np.isnan(agg[40_000])
+    assert np.isfinite(np.delete(agg, [12_345, 40_000])).all()
+    assert np.isfinite(st[0, HEAD]) and np.isinf(st[0, HEAD + 1]) and np.isnan(st[0, HEAD + 2])
+
+
+# ------------------------------------------------------------------ behaviour of the entry point
+def test_bitwise_reproducible_and_stats_only():
+    w = W.config("C2", device=DEV, P=3_000_001)
+    a1, s1 = run_gpu(w)
+    a2, s2 = run_gpu(w)
+    assert np.array_equal(a1, a2) and np.array_equal(s1, s2)
+    a3, s3 = run_gpu(w, stats_only=True)
+    assert a3 is None and np.array_equal(s1, s3)
+
+
+def test_other_stream_and_caller_buffers(oracle_mod):
+    w = W.config("C1", device=DEV, P=400_003)
+    out_agg = torch.full((w.P,), 7.0, dtype=torch.float32, device=DEV)
+    out_st = torch.full((1, HEAD + 2 * w.K), 7.0, dtype=torch.float64, device=DEV)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        for _ in range(3):          # steady state reuses the cached plan and workspace
+            a, st = D.dynamix_grad_aggregate_stats_ex(w.grads, w.batch_sizes, out_agg=out_agg,
+                                                      out_stats=out_st, stream=s)
+    s.synchronize()
+    assert a is out_agg and st is out_st
+    ragg, rst = run_oracle(oracle_mod, w)
+    compare(out_agg.cpu().numpy(), out_st.cpu().numpy(), ragg, rst, w.batch_sizes, where="stream")
+    assert D.dynamix_release_cached() == 0
+    a2, st2 = run_gpu(w)
+    assert np.array_equal(a2, out_agg.cpu().numpy())
+
+
+def test_permuting_workers_permutes_their_entries(oracle_mod):
+    w = W.config("C2", device=DEV, P=500_001)
+    _, st = run_gpu(w)
+    perm = np.random.default_rng(0).permutation(w.K)
+    w2 = W.Workload(name="perm", K=w.K, P=w.P, dtype=w.dtype, batch_sizes=w.batch_sizes[perm],
+                    grads=[w.grads[p] for p in perm], segment_offsets=None, m=w.m,
+                    sigma=w.sigma, mu_sqnorm=w.mu_sqnorm)
+    _, st2 = run_gpu(w2)
+    # a worker's own squared norm does not depend on its slot; the aggregate only to rounding
+    assert np.array_equal(st2[0, HEAD:HEAD + w.K], st[0, HEAD:HEAD + w.K][perm])
+    np.testing.assert_allclose(st2[0, :7], st[0, :7], rtol=1e-5)
