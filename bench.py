@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=16_000_000,
                     help="elements per worker the CPU oracle is timed on (0: skip)")
     ap.add_argument("--cpu-threads", type=int, default=16)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain elementwise copy of 2^28 floats (1 GiB read, 1 GiB "
+                         "written) three times, as the known-size reference for HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this path runs on one GPU only (no sharding, no collectives); "
@@ -77,6 +80,14 @@ def main():
     def step():
         D.dynamix_grad_aggregate_stats_ex(w.grads, w.batch_sizes, w.segment_offsets,
                                           out_agg=out_agg, out_stats=out_stats, stream=stream)
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

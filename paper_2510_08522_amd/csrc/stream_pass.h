@@ -65,6 +65,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* base, in
 }
 
 constexpr int kNT = 2;               // cache-policy bit "non-temporal": data is touched once
+constexpr int kLoadPolicy = kNT;     // gradient loads of interior tiles
+constexpr int kStorePolicy = kNT;    // aggregate stores of interior tiles
 constexpr int kMasked = 0x7ffffff0;  // a lane offset beyond every tile: the access is dropped
 
 template <int K, int DT, int U>
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                     for (int k = 0; k < K; ++k)
                         x[u][k] = __builtin_amdgcn_raw_buffer_load_b128(
                             tile_rsrc(a.g[k], v0 * 16, kBlock * U * 16),
-                            (u * kBlock + tid) * 16, 0, kNT);
+                            (u * kBlock + tid) * 16, 0, kLoadPolicy);
             } else {
                 // edge tile (segment boundary or ragged tail): element-wise loads whose lane
                 // offset is pushed out of range for masked elements, which then read as zero
@@ -135,45 +137,63 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int64_t v = v0 + (u * kBlock + tid);
+                // pass 1 over the K values in registers: the weighted aggregate
                 float G[VEC];
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) G[c] = 0.f;
-                if constexpr (DT == kF32) {
 #pragma unroll
-                    for (int k = 0; k < K; ++k) {
-                        const float wk = a.w[k];
+                for (int k = 0; k < K; ++k) {
+                    const float wk = a.w[k];
 #pragma unroll
-                        for (int c = 0; c < 4; ++c)
-                            G[c] = __builtin_fmaf(wk, __uint_as_float(x[u][k][c]), G[c]);
-                    }
-#pragma unroll
-                    for (int k = 0; k < K; ++k) {
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            const float g = __uint_as_float(x[u][k][c]);
-                            n[k] = __builtin_fmaf(g, g, n[k]);
-                            const float t = g - G[c];
-                            d[k] = __builtin_fmaf(t, t, d[k]);
-                        }
-                    }
-                } else {
-                    // bf16 is the upper half of fp32: widening is a shift or a mask, exact
-#pragma unroll
-                    for (int k = 0; k < K; ++k) {
-                        const float wk = a.w[k];
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            const uint32_t q = x[u][k][c];
+                    for (int c = 0; c < 4; ++c) {
+                        const uint32_t q = x[u][k][c];
+                        if constexpr (DT == kF32) {
+                            G[c] = __builtin_fmaf(wk, __uint_as_float(q), G[c]);
+                        } else {
+                            // bf16 is the upper half of fp32: widening is a shift or a mask, exact
                             G[2 * c] = __builtin_fmaf(wk, __uint_as_float(q << 16), G[2 * c]);
                             G[2 * c + 1] =
                                 __builtin_fmaf(wk, __uint_as_float(q & 0xffff0000u), G[2 * c + 1]);
                         }
                     }
+                }
 #pragma unroll
-                    for (int k = 0; k < K; ++k) {
+                for (int c = 0; c < VEC; ++c) A = __builtin_fmaf(G[c], G[c], A);
+
+                // the only write of the pass, issued as soon as G is known
+                if (a.out_agg != nullptr) {
+                    const __amdgpu_buffer_rsrc_t r =
+                        tile_rsrc(a.out_agg, v0 * (VEC * 4), kBlock * U * VEC * 4);
+                    const int o = (u * kBlock + tid) * (VEC * 4);
+                    if (interior) {
 #pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            uint32_t q = x[u][k][c];
+                        for (int h = 0; h < VEC / 4; ++h) {
+                            u32x4 q = {__float_as_uint(G[4 * h]), __float_as_uint(G[4 * h + 1]),
+                                       __float_as_uint(G[4 * h + 2]), __float_as_uint(G[4 * h + 3])};
+                            __builtin_amdgcn_raw_buffer_store_b128(q, r, o + 16 * h, 0, kStorePolicy);
+                        }
+                    } else {
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) {
+                            const int64_t e = v * VEC + c;
+                            const int oc = (e >= pc.e_lo && e < pc.e_hi) ? o + 4 * c : kMasked;
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(G[c]), r, oc, 0, 0);
+                        }
+                    }
+                }
+
+                // pass 2 over the same registers: squared norms and squared deviations
+#pragma unroll
+                for (int k = 0; k < K; ++k) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        uint32_t q = x[u][k][c];
+                        if constexpr (DT == kF32) {
+                            const float g = __uint_as_float(q);
+                            n[k] = __builtin_fmaf(g, g, n[k]);
+                            const float t = g - G[c];
+                            d[k] = __builtin_fmaf(t, t, d[k]);
+                        } else {
                             // keep the packed pair live and widen it again here: without this
                             // the compiler holds all 8K widened values and halves the occupancy
                             asm volatile("" : "+v"(q));
@@ -184,29 +204,6 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                             const float t0 = g0 - G[2 * c], t1 = g1 - G[2 * c + 1];
                             d[k] = __builtin_fmaf(t0, t0, d[k]);
                             d[k] = __builtin_fmaf(t1, t1, d[k]);
-                        }
-                    }
-                }
-#pragma unroll
-                for (int c = 0; c < VEC; ++c) A = __builtin_fmaf(G[c], G[c], A);
-
-                if (a.out_agg != nullptr) {
-                    const __amdgpu_buffer_rsrc_t r =
-                        tile_rsrc(a.out_agg, v0 * (VEC * 4), kBlock * U * VEC * 4);
-                    const int o = (u * kBlock + tid) * (VEC * 4);
-                    if (interior) {
-#pragma unroll
-                        for (int h = 0; h < VEC / 4; ++h) {
-                            u32x4 q = {__float_as_uint(G[4 * h]), __float_as_uint(G[4 * h + 1]),
-                                       __float_as_uint(G[4 * h + 2]), __float_as_uint(G[4 * h + 3])};
-                            __builtin_amdgcn_raw_buffer_store_b128(q, r, o + 16 * h, 0, kNT);
-                        }
-                    } else {
-#pragma unroll
-                        for (int c = 0; c < VEC; ++c) {
-                            const int64_t e = v * VEC + c;
-                            const int oc = (e >= pc.e_lo && e < pc.e_hi) ? o + 4 * c : kMasked;
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(G[c]), r, oc, 0, 0);
                         }
                     }
                 }
