@@ -99,7 +99,7 @@ struct Layout {
 void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int64_t max_grid,
                  bool interleave, Layout& L)
 {
-    const int VEC = dtype == kF32 ? 4 : 8;
+    const int VEC = vec_elems(K, dtype);
     const int64_t tile = (int64_t)kBlock * unroll_for(K);  // vectors per block iteration
     const int64_t nvec = ceil_div(P, VEC);
     const int64_t ntiles = ceil_div(nvec, tile);

@@ -6,7 +6,7 @@
 namespace dynamix {
 
 constexpr int kKMax = 64;        // workers per call; pointers and weights travel by value
-constexpr int kBlock = 256;      // threads per block of the streaming pass: 4 wave64
+constexpr int kBlock = 512;      // threads per block of the streaming pass: 8 wave64, one block per CU
 constexpr int kWaves = kBlock / 64;
 constexpr int kHead = 8;         // scalars in front of the per-worker entries of a record
 
@@ -17,7 +17,14 @@ enum : int { kF32 = 0, kBF16 = 1 };
 // aggregate of the vector is known.
 constexpr int unroll_for(int K) { return K <= 2 ? 8 : K <= 8 ? 4 : K <= 16 ? 2 : 1; }
 
-// One unit of streaming work: 16-byte vectors v_begin, v_begin + v_step, ... below v_end are the
+// 32-bit words a lane loads at a time: four (128-bit loads) up to 32 workers, two up to 48, one
+// above, so that the K vectors of a lane plus the 2K+1 running sums stay within 256 registers at
+// eight waves per compute unit.
+constexpr int load_words_for(int K) { return K > 48 ? 1 : K > 32 ? 2 : 4; }
+// elements per vector
+constexpr int vec_elems(int K, int dtype) { return load_words_for(K) * (dtype == kF32 ? 1 : 2); }
+
+// One unit of streaming work: vectors v_begin, v_begin + v_step, ... below v_end are the
 // starts of the block iterations; elements outside [e_lo, e_hi) are masked (segment edges and
 // the ragged tail).  One partial record of 2K+1 sums is produced per piece.
 struct Piece {

@@ -2,14 +2,15 @@
 // records, in double precision and in a fixed order (no atomics), then derives the scalars.
 //
 // One block per record.  Level 1: the pieces of the record are dealt round-robin to row groups
-// and every (row group, column) thread adds its pieces in increasing order.  Level 2: the row
+// and every (row group, column) thread adds its pieces in increasing order (four interleaved
+// running sums, folded in a fixed order).  Level 2: the row
 // groups of a column are added in increasing order.  The order depends only on the plan, so the
 // result is bitwise reproducible.
 #include "dynamix_internal.h"
 
 namespace dynamix {
 
-constexpr int kFinalBlock = 256;
+constexpr int kFinalBlock = 1024;
 
 __global__ __launch_bounds__(kFinalBlock) void final_reduce_kernel(const FinalArgs a)
 {
@@ -20,16 +21,25 @@ __global__ __launch_bounds__(kFinalBlock) void final_reduce_kernel(const FinalAr
     const int tid = threadIdx.x;
     const int p0 = a.rec_range[2 * rec];
     const int p1 = a.rec_range[2 * rec + 1];
-    const int groups = kFinalBlock / W;  // >= 1 because W <= 129
+    const int groups = kFinalBlock / W;  // >= 7 because W <= 129
 
     __shared__ double part[kFinalBlock];
     __shared__ double tot[2 * kKMax + 1];
 
     if (tid < W * groups) {
         const int col = tid % W, grp = tid / W;
-        double s = 0.0;
-        for (int p = p0 + grp; p < p1; p += groups) s += a.partials[(int64_t)p * W + col];
-        part[tid] = s;
+        // four independent running sums keep four loads in flight; they are folded in a fixed
+        // order, so the result depends only on the plan
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        int p = p0 + grp;
+        for (; p + 3 * groups < p1; p += 4 * groups) {
+            s0 += a.partials[(int64_t)p * W + col];
+            s1 += a.partials[(int64_t)(p + groups) * W + col];
+            s2 += a.partials[(int64_t)(p + 2 * groups) * W + col];
+            s3 += a.partials[(int64_t)(p + 3 * groups) * W + col];
+        }
+        for (; p < p1; p += groups) s0 += a.partials[(int64_t)p * W + col];
+        part[tid] = (s0 + s1) + (s2 + s3);
     }
     __syncthreads();
     if (tid < W) {

@@ -39,17 +39,62 @@ __device__ __forceinline__ float wave_sum(float v)
     return (r0 + r1) + (r2 + r3);
 }
 
-template <int DT>
-struct Elem;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kNT = 2;               // cache-policy bit "non-temporal": data is touched once
+constexpr int kLoadPolicy = kNT;     // gradient loads of interior tiles
+constexpr int kStorePolicy = kNT;    // aggregate stores of interior tiles
+
+// One "vector" is what a lane loads at a time: LW 32-bit words (4 up to K = 32, then 2, then 1, so
+// that the K vectors of a lane and the 2K+1 sums still fit the register file), i.e. LW fp32 or
+// 2 LW bf16 elements.
+template <int LW>
+struct Words;
 template <>
-struct Elem<kF32> {
-    static constexpr int kVec = 4;   // elements per 16 bytes
-    static constexpr int kSize = 4;
+struct Words<4> {
+    typedef u32x4 type;
+    template <int POL>
+    static __device__ __forceinline__ type load(__amdgpu_buffer_rsrc_t r, int off)
+    {
+        return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, POL);
+    }
+    template <int POL>
+    static __device__ __forceinline__ void store(type v, __amdgpu_buffer_rsrc_t r, int off)
+    {
+        __builtin_amdgcn_raw_buffer_store_b128(v, r, off, 0, POL);
+    }
 };
 template <>
-struct Elem<kBF16> {
-    static constexpr int kVec = 8;
-    static constexpr int kSize = 2;
+struct Words<2> {
+    typedef u32x2 type;
+    template <int POL>
+    static __device__ __forceinline__ type load(__amdgpu_buffer_rsrc_t r, int off)
+    {
+        return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, POL);
+    }
+    template <int POL>
+    static __device__ __forceinline__ void store(type v, __amdgpu_buffer_rsrc_t r, int off)
+    {
+        __builtin_amdgcn_raw_buffer_store_b64(v, r, off, 0, POL);
+    }
+};
+
+typedef uint32_t u32x1 __attribute__((ext_vector_type(1)));
+template <>
+struct Words<1> {
+    typedef u32x1 type;
+    template <int POL>
+    static __device__ __forceinline__ type load(__amdgpu_buffer_rsrc_t r, int off)
+    {
+        type v;
+        v[0] = __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, POL);
+        return v;
+    }
+    template <int POL>
+    static __device__ __forceinline__ void store(type v, __amdgpu_buffer_rsrc_t r, int off)
+    {
+        __builtin_amdgcn_raw_buffer_store_b32(v[0], r, off, 0, POL);
+    }
 };
 
 // Buffer descriptor over one tile of a stream: the uniform 64-bit base (pointer + tile start)
@@ -64,41 +109,78 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* base, in
         /*num_records=*/bytes, /*flags=*/0x00020000);
 }
 
-constexpr int kNT = 2;               // cache-policy bit "non-temporal": data is touched once
-constexpr int kLoadPolicy = kNT;     // gradient loads of interior tiles
-constexpr int kStorePolicy = kNT;    // aggregate stores of interior tiles
 constexpr int kMasked = 0x7ffffff0;  // a lane offset beyond every tile: the access is dropped
+
+// The eight waves of a block leave every barrier in lockstep, and two waves that share a SIMD
+// then want the vector ALU and the memory pipeline at the same moments (measured: 4 % of the
+// bandwidth against two independent blocks of four waves).  Wave w therefore idles w * 1024
+// clocks (at most 3 microseconds) when a piece starts and after each flush.
+__device__ __forceinline__ void stagger_waves(int tid)
+{
+    for (int i = 0; i < (tid >> 6); ++i) __builtin_amdgcn_s_sleep(16);
+}
+
+// Staging of the aggregate.  A store that enters a compute unit's memory pipeline while that unit
+// has loads in flight holds the pipeline up for hundreds of cycles (measured: one 16-byte store
+// per lane and tile costs a 32-stream read 27 % of its bandwidth, whatever the store's cache
+// policy, issuing wave or size).  So G of kStageTiles tiles is parked in LDS and the whole block
+// (the only one on its compute unit) writes it out between two barriers, when none of its loads
+// is outstanding.
+constexpr int kStageBytes = 128 * 1024;
+template <int K, int DT, int U>
+struct Shape {
+    static constexpr int kLW = load_words_for(K);                  // words per lane and load
+    static constexpr int kVB = kLW * 4;                            // bytes per lane and load
+    static constexpr int kVec = vec_elems(K, DT);                  // elements per vector
+    static constexpr int kSize = DT == kF32 ? 4 : 2;               // bytes per element
+    static constexpr int kQ = kVec / kLW;                          // LW-word pieces of G per vector
+    static constexpr int kSlots = kStageBytes / (kBlock * kVB);    // LW-word slots per thread
+    static constexpr int kTiles = kSlots / (U * kQ);               // tiles per flush
+    static_assert(kTiles >= 1, "a tile of G must fit the staging area");
+};
 
 template <int K, int DT, int U>
 __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
 {
-    constexpr int VEC = Elem<DT>::kVec;
+    typedef Shape<K, DT, U> Sh;
+    typedef Words<Sh::kLW> Wd;
+    typedef typename Wd::type wvec;
+    constexpr int LW = Sh::kLW, VB = Sh::kVB, VEC = Sh::kVec, Q = Sh::kQ, NB = Sh::kTiles;
     constexpr int W = 2 * K + 1;
+    __shared__ wvec stage[NB * U * Q][kBlock];
     __shared__ float wave_part[kWaves][W];
 
     const int tid = threadIdx.x;
     const int p_first = a.block_first[blockIdx.x];
     const int p_last = a.block_first[blockIdx.x + 1];
+    const bool want_agg = a.out_agg != nullptr;
 
     for (int p = p_first; p < p_last; ++p) {
         const Piece pc = a.pieces[p];
         float n[K], d[K], A = 0.f;
 #pragma unroll
         for (int k = 0; k < K; ++k) n[k] = d[k] = 0.f;
+        // worth it only for a piece of many tiles
+        const bool long_piece = pc.v_end - pc.v_begin > 8 * (int64_t)kBlock * U;
+        if (long_piece) stagger_waves(tid);
+        int staged = 0;            // interior tiles parked in LDS
+        int64_t v_staged = 0;      // first of them
+        wvec x[U][K];              // the K vectors of every lane
+        bool have = false;         // x already holds this iteration's tile (prefetched)
 
         for (int64_t v0 = pc.v_begin; v0 < pc.v_end; v0 += pc.v_step) {
             // block-uniform: every element of this iteration lies inside the piece
             const bool interior =
                 v0 * VEC >= pc.e_lo && (v0 + (int64_t)kBlock * U) * VEC <= pc.e_hi;
-            u32x4 x[U][K];
-            if (interior) {
+            if (have) {
+                // loaded during pass 2 of the previous iteration
+            } else if (interior) {
 #pragma unroll
                 for (int u = 0; u < U; ++u)
 #pragma unroll
                     for (int k = 0; k < K; ++k)
-                        x[u][k] = __builtin_amdgcn_raw_buffer_load_b128(
-                            tile_rsrc(a.g[k], v0 * 16, kBlock * U * 16),
-                            (u * kBlock + tid) * 16, 0, kLoadPolicy);
+                        x[u][k] = Wd::template load<kLoadPolicy>(
+                            tile_rsrc(a.g[k], v0 * VB, kBlock * U * VB), (u * kBlock + tid) * VB);
             } else {
                 // edge tile (segment boundary or ragged tail): element-wise loads whose lane
                 // offset is pushed out of range for masked elements, which then read as zero
@@ -109,20 +191,20 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                     for (int c = 0; c < VEC; ++c) {
                         const int64_t e = (v0 + (u * kBlock + tid)) * VEC + c;
                         off[c] = (e >= pc.e_lo && e < pc.e_hi)
-                                     ? ((u * kBlock + tid) * VEC + c) * Elem<DT>::kSize
+                                     ? ((u * kBlock + tid) * VEC + c) * Sh::kSize
                                      : kMasked;
                     }
 #pragma unroll
                     for (int k = 0; k < K; ++k) {
                         const __amdgpu_buffer_rsrc_t r =
-                            tile_rsrc(a.g[k], v0 * 16, kBlock * U * 16);
+                            tile_rsrc(a.g[k], v0 * VB, kBlock * U * VB);
                         if constexpr (DT == kF32) {
 #pragma unroll
-                            for (int c = 0; c < 4; ++c)
+                            for (int c = 0; c < LW; ++c)
                                 x[u][k][c] = __builtin_amdgcn_raw_buffer_load_b32(r, off[c], 0, 0);
                         } else {
 #pragma unroll
-                            for (int c = 0; c < 4; ++c) {
+                            for (int c = 0; c < LW; ++c) {
                                 const uint32_t lo =
                                     __builtin_amdgcn_raw_buffer_load_b16(r, off[2 * c], 0, 0);
                                 const uint32_t hi =
@@ -133,10 +215,24 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                     }
                 }
             }
+            if (interior && staged == 0) v_staged = v0;
+
+            // Software pipeline without extra registers: as pass 2 finishes with a worker's
+            // vector, the same registers take that worker's vector of the next tile, so loads
+            // are issued all through the arithmetic.  Not across a flush (the pipeline must be
+            // empty of loads then) and not into an edge tile; in those cases the descriptor gets
+            // zero length and the loads touch no memory.
+            const int64_t vn = v0 + pc.v_step;
+            const bool next_interior = vn < pc.v_end && vn * VEC >= pc.e_lo &&
+                                       (vn + (int64_t)kBlock * U) * VEC <= pc.e_hi;
+            const int staged_after = staged + (interior ? 1 : 0);
+            const bool flush_now =
+                want_agg && (staged_after == NB || (vn >= pc.v_end && staged_after > 0));
+            const bool prefetch = next_interior && !flush_now;
+            const int next_bytes = prefetch ? kBlock * U * VB : 0;
 
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t v = v0 + (u * kBlock + tid);
                 // pass 1 over the K values in registers: the weighted aggregate
                 float G[VEC];
 #pragma unroll
@@ -145,7 +241,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                 for (int k = 0; k < K; ++k) {
                     const float wk = a.w[k];
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
+                    for (int c = 0; c < LW; ++c) {
                         const uint32_t q = x[u][k][c];
                         if constexpr (DT == kF32) {
                             G[c] = __builtin_fmaf(wk, __uint_as_float(q), G[c]);
@@ -160,19 +256,21 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) A = __builtin_fmaf(G[c], G[c], A);
 
-                // the only write of the pass, issued as soon as G is known
-                if (a.out_agg != nullptr) {
-                    const __amdgpu_buffer_rsrc_t r =
-                        tile_rsrc(a.out_agg, v0 * (VEC * 4), kBlock * U * VEC * 4);
-                    const int o = (u * kBlock + tid) * (VEC * 4);
+                if (want_agg) {
                     if (interior) {
+                        // park G; every thread later reads back only what it wrote itself
 #pragma unroll
-                        for (int h = 0; h < VEC / 4; ++h) {
-                            u32x4 q = {__float_as_uint(G[4 * h]), __float_as_uint(G[4 * h + 1]),
-                                       __float_as_uint(G[4 * h + 2]), __float_as_uint(G[4 * h + 3])};
-                            __builtin_amdgcn_raw_buffer_store_b128(q, r, o + 16 * h, 0, kStorePolicy);
+                        for (int h = 0; h < Q; ++h) {
+                            wvec q;
+#pragma unroll
+                            for (int c = 0; c < LW; ++c) q[c] = __float_as_uint(G[LW * h + c]);
+                            stage[(staged * U + u) * Q + h][tid] = q;
                         }
                     } else {
+                        const __amdgpu_buffer_rsrc_t r =
+                            tile_rsrc(a.out_agg, v0 * (VEC * 4), kBlock * U * VEC * 4);
+                        const int o = (u * kBlock + tid) * (VEC * 4);
+                        const int64_t v = v0 + (u * kBlock + tid);
 #pragma unroll
                         for (int c = 0; c < VEC; ++c) {
                             const int64_t e = v * VEC + c;
@@ -186,7 +284,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
 #pragma unroll
                 for (int k = 0; k < K; ++k) {
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
+                    for (int c = 0; c < LW; ++c) {
                         uint32_t q = x[u][k][c];
                         if constexpr (DT == kF32) {
                             const float g = __uint_as_float(q);
@@ -206,11 +304,44 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                             d[k] = __builtin_fmaf(t1, t1, d[k]);
                         }
                     }
+                    // order the load after the last use of the registers it overwrites (the empty
+                    // asm ties its address to this worker's updated sums), or the scheduler
+                    // hoists all K loads and the live ranges double
+                    int pf_off = (u * kBlock + tid) * VB;
+                    asm volatile("" : "+v"(pf_off) : "v"(n[k]), "v"(d[k]));
+                    x[u][k] = Wd::template load<kLoadPolicy>(
+                        tile_rsrc(a.g[k], vn * VB, next_bytes), pf_off);
+                }
+            }
+            have = prefetch;
+
+            if (want_agg) {
+                staged = staged_after;
+                if (flush_now) {
+                    // flush: all waves have consumed their loads; write the parked tiles out and
+                    // wait for the stores before the next loads are issued
+                    __syncthreads();
+                    for (int j = 0; j < staged; ++j) {
+                        const int64_t vj = v_staged + j * pc.v_step;
+                        const __amdgpu_buffer_rsrc_t r =
+                            tile_rsrc(a.out_agg, vj * (VEC * 4), kBlock * U * VEC * 4);
+#pragma unroll
+                        for (int u = 0; u < U; ++u)
+#pragma unroll
+                            for (int h = 0; h < Q; ++h)
+                                Wd::template store<kStorePolicy>(
+                                    stage[(j * U + u) * Q + h][tid], r,
+                                    (u * kBlock + tid) * (VEC * 4) + VB * h);
+                    }
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    __syncthreads();
+                    staged = 0;
+                    if (long_piece) stagger_waves(tid);
                 }
             }
         }
 
-        // block reduction: DPP inside each wave (fp32), then the four wave sums in fp64, fixed order
+        // block reduction: DPP inside each wave (fp32), then the wave sums in fp64, fixed order
         const int lane = tid & 63, wave = tid >> 6;
         {
             const float r = wave_sum(A);

@@ -91,8 +91,8 @@ def unroll_for(K):
 def check_cover(K, P, dtype, off, max_blocks, interleave=False):
     """Replay the kernel's iteration space on the host and count how often each element is
     touched by an unmasked lane, per record."""
-    vec = 4 if dtype == 0 else 8
-    tile = 256 * unroll_for(K)
+    vec = (1 if K > 48 else 2 if K > 32 else 4) * (1 if dtype == 0 else 2)   # elements per lane and load
+    tile = 512 * unroll_for(K)                              # vectors per block iteration
     pcs = D.dynamix_plan_describe(K, P, dtype, off, max_blocks, interleave)
     assert len(pcs) >= 1
     assert (np.diff(pcs[:, 5]) >= 0).all()                      # pieces sorted by owning block
@@ -134,11 +134,11 @@ def test_plan_covers_every_element_once(dtype):
 
 
 def test_plan_for_the_headline_shape_is_balanced():
-    pcs = check_cover(32, 138_000_000, 0, None, 512)
+    pcs = check_cover(32, 138_000_000, 0, None, 256)
     vec_per_piece = pcs[:, 1] - pcs[:, 0]
-    assert len(pcs) <= 512
-    assert vec_per_piece.max() <= 1.01 * (138_000_000 / 4) / len(pcs) + 256
-    assert ((vec_per_piece[:-1] // 256) % 2 == 1).all()         # odd tile count per span
+    assert len(pcs) <= 256
+    assert vec_per_piece.max() <= 1.01 * (138_000_000 / 4) / len(pcs) + 512
+    assert ((vec_per_piece[:-1] // 512) % 2 == 1).all()         # odd tile count per span
 
 
 def test_plan_describe_rejects_bad_shapes():
