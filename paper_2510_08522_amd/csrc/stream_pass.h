@@ -147,6 +147,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
     typedef typename Wd::type wvec;
     constexpr int LW = Sh::kLW, VB = Sh::kVB, VEC = Sh::kVec, Q = Sh::kQ, NB = Sh::kTiles;
     constexpr int W = 2 * K + 1;
+    constexpr int64_t TILE = (int64_t)kBlock * U;   // vectors per block iteration
     __shared__ wvec stage[NB * U * Q][kBlock];
     __shared__ float wave_part[kWaves][W];
 
@@ -160,185 +161,238 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
         float n[K], d[K], A = 0.f;
 #pragma unroll
         for (int k = 0; k < K; ++k) n[k] = d[k] = 0.f;
-        // worth it only for a piece of many tiles
-        const bool long_piece = pc.v_end - pc.v_begin > 8 * (int64_t)kBlock * U;
-        if (long_piece) stagger_waves(tid);
-        int staged = 0;            // interior tiles parked in LDS
-        int64_t v_staged = 0;      // first of them
-        wvec x[U][K];              // the K vectors of every lane
-        bool have = false;         // x already holds this iteration's tile (prefetched)
 
-        for (int64_t v0 = pc.v_begin; v0 < pc.v_end; v0 += pc.v_step) {
-            // block-uniform: every element of this iteration lies inside the piece
-            const bool interior =
-                v0 * VEC >= pc.e_lo && (v0 + (int64_t)kBlock * U) * VEC <= pc.e_hi;
-            if (have) {
-                // loaded during pass 2 of the previous iteration
-            } else if (interior) {
+        // block-uniform: every element of the tile that starts at vector v lies inside the piece
+        auto interior = [&](int64_t v) {
+            return v < pc.v_end && v * VEC >= pc.e_lo && (v + TILE) * VEC <= pc.e_hi;
+        };
+        // pass 1 over the K vectors of one lane: the weighted aggregate, k ascending
+        auto pass1 = [&](const wvec (&xu)[K], float (&Gu)[VEC]) {
 #pragma unroll
-                for (int u = 0; u < U; ++u)
+            for (int c = 0; c < VEC; ++c) Gu[c] = 0.f;
 #pragma unroll
-                    for (int k = 0; k < K; ++k)
-                        x[u][k] = Wd::template load<kLoadPolicy>(
-                            tile_rsrc(a.g[k], v0 * VB, kBlock * U * VB), (u * kBlock + tid) * VB);
-            } else {
-                // edge tile (segment boundary or ragged tail): element-wise loads whose lane
-                // offset is pushed out of range for masked elements, which then read as zero
+            for (int k = 0; k < K; ++k) {
+                const float wk = a.w[k];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    int off[VEC];
-#pragma unroll
-                    for (int c = 0; c < VEC; ++c) {
-                        const int64_t e = (v0 + (u * kBlock + tid)) * VEC + c;
-                        off[c] = (e >= pc.e_lo && e < pc.e_hi)
-                                     ? ((u * kBlock + tid) * VEC + c) * Sh::kSize
-                                     : kMasked;
+                for (int c = 0; c < LW; ++c) {
+                    const uint32_t q = xu[k][c];
+                    if constexpr (DT == kF32) {
+                        Gu[c] = __builtin_fmaf(wk, __uint_as_float(q), Gu[c]);
+                    } else {
+                        // bf16 is the upper half of fp32: widening is a shift or a mask, exact
+                        Gu[2 * c] = __builtin_fmaf(wk, __uint_as_float(q << 16), Gu[2 * c]);
+                        Gu[2 * c + 1] =
+                            __builtin_fmaf(wk, __uint_as_float(q & 0xffff0000u), Gu[2 * c + 1]);
                     }
+                }
+            }
 #pragma unroll
-                    for (int k = 0; k < K; ++k) {
-                        const __amdgpu_buffer_rsrc_t r =
-                            tile_rsrc(a.g[k], v0 * VB, kBlock * U * VB);
-                        if constexpr (DT == kF32) {
+            for (int c = 0; c < VEC; ++c) A = __builtin_fmaf(Gu[c], Gu[c], A);
+        };
+        // pass 2 for worker k: squared norm and squared deviation from the aggregate
+        auto pass2 = [&](const wvec& xk, const float (&Gu)[VEC], int k) {
 #pragma unroll
-                            for (int c = 0; c < LW; ++c)
-                                x[u][k][c] = __builtin_amdgcn_raw_buffer_load_b32(r, off[c], 0, 0);
-                        } else {
+            for (int c = 0; c < LW; ++c) {
+                uint32_t q = xk[c];
+                // pins this read between the loads around it (and, for bf16, keeps the packed
+                // pair live instead of all 8K widened values)
+                asm volatile("" : "+v"(q));
+                if constexpr (DT == kF32) {
+                    const float g = __uint_as_float(q);
+                    n[k] = __builtin_fmaf(g, g, n[k]);
+                    const float t = g - Gu[c];
+                    d[k] = __builtin_fmaf(t, t, d[k]);
+                } else {
+                    const float g0 = __uint_as_float(q << 16);
+                    const float g1 = __uint_as_float(q & 0xffff0000u);
+                    n[k] = __builtin_fmaf(g0, g0, n[k]);
+                    n[k] = __builtin_fmaf(g1, g1, n[k]);
+                    const float t0 = g0 - Gu[2 * c], t1 = g1 - Gu[2 * c + 1];
+                    d[k] = __builtin_fmaf(t0, t0, d[k]);
+                    d[k] = __builtin_fmaf(t1, t1, d[k]);
+                }
+            }
+        };
+        // An edge tile (segment boundary at any element, ragged tail): element-wise loads and
+        // stores whose lane offset is pushed out of the descriptor's range for masked elements,
+        // which then read as zero and are not written.  Rare, so it favours few registers over
+        // speed: the tile is read twice (once per pass), eight workers at a time.
+        auto edge_load = [&](int k, int64_t v0, const int (&off)[VEC]) {
+            const __amdgpu_buffer_rsrc_t r = tile_rsrc(a.g[k], v0 * VB, kBlock * U * VB);
+            wvec xe;
 #pragma unroll
-                            for (int c = 0; c < LW; ++c) {
-                                const uint32_t lo =
-                                    __builtin_amdgcn_raw_buffer_load_b16(r, off[2 * c], 0, 0);
-                                const uint32_t hi =
-                                    __builtin_amdgcn_raw_buffer_load_b16(r, off[2 * c + 1], 0, 0);
-                                x[u][k][c] = (lo & 0xffffu) | (hi << 16);
+            for (int c = 0; c < LW; ++c) {
+                if constexpr (DT == kF32) {
+                    xe[c] = __builtin_amdgcn_raw_buffer_load_b32(r, off[c], 0, 0);
+                } else {
+                    const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(r, off[2 * c], 0, 0);
+                    const uint32_t hi =
+                        __builtin_amdgcn_raw_buffer_load_b16(r, off[2 * c + 1], 0, 0);
+                    xe[c] = (lo & 0xffffu) | (hi << 16);
+                }
+            }
+            return xe;
+        };
+        auto edge_tile = [&](int64_t v0) {
+            constexpr int CH = 8;   // workers whose loads are in flight together
+#pragma unroll 1
+            for (int u = 0; u < U; ++u) {
+                int off[VEC];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) {
+                    const int64_t e = (v0 + (u * kBlock + tid)) * VEC + c;
+                    off[c] = (e >= pc.e_lo && e < pc.e_hi)
+                                 ? ((u * kBlock + tid) * VEC + c) * Sh::kSize
+                                 : kMasked;
+                }
+                float Ge[VEC];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) Ge[c] = 0.f;
+#pragma unroll
+                for (int k0 = 0; k0 < K; k0 += CH) {
+                    // start this batch only when the one before has been consumed
+                    asm volatile("" : "+v"(off[0]) : "v"(Ge[0]));
+                    wvec xe[CH];
+#pragma unroll
+                    for (int j = 0; j < CH; ++j)
+                        if (k0 + j < K) xe[j] = edge_load(k0 + j, v0, off);
+#pragma unroll
+                    for (int j = 0; j < CH; ++j) {
+                        if (k0 + j >= K) continue;
+                        const float wk = a.w[k0 + j];
+#pragma unroll
+                        for (int c = 0; c < LW; ++c) {
+                            const uint32_t q = xe[j][c];
+                            if constexpr (DT == kF32) {
+                                Ge[c] = __builtin_fmaf(wk, __uint_as_float(q), Ge[c]);
+                            } else {
+                                Ge[2 * c] = __builtin_fmaf(wk, __uint_as_float(q << 16), Ge[2 * c]);
+                                Ge[2 * c + 1] = __builtin_fmaf(
+                                    wk, __uint_as_float(q & 0xffff0000u), Ge[2 * c + 1]);
                             }
                         }
                     }
                 }
-            }
-            if (interior && staged == 0) v_staged = v0;
-
-            // Software pipeline without extra registers: as pass 2 finishes with a worker's
-            // vector, the same registers take that worker's vector of the next tile, so loads
-            // are issued all through the arithmetic.  Not across a flush (the pipeline must be
-            // empty of loads then) and not into an edge tile; in those cases the descriptor gets
-            // zero length and the loads touch no memory.
-            const int64_t vn = v0 + pc.v_step;
-            const bool next_interior = vn < pc.v_end && vn * VEC >= pc.e_lo &&
-                                       (vn + (int64_t)kBlock * U) * VEC <= pc.e_hi;
-            const int staged_after = staged + (interior ? 1 : 0);
-            const bool flush_now =
-                want_agg && (staged_after == NB || (vn >= pc.v_end && staged_after > 0));
-            const bool prefetch = next_interior && !flush_now;
-            const int next_bytes = prefetch ? kBlock * U * VB : 0;
-
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                // pass 1 over the K values in registers: the weighted aggregate
-                float G[VEC];
+                for (int c = 0; c < VEC; ++c) A = __builtin_fmaf(Ge[c], Ge[c], A);
+                if (want_agg) {
+                    const __amdgpu_buffer_rsrc_t r =
+                        tile_rsrc(a.out_agg, v0 * (VEC * 4), kBlock * U * VEC * 4);
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) G[c] = 0.f;
-#pragma unroll
-                for (int k = 0; k < K; ++k) {
-                    const float wk = a.w[k];
-#pragma unroll
-                    for (int c = 0; c < LW; ++c) {
-                        const uint32_t q = x[u][k][c];
-                        if constexpr (DT == kF32) {
-                            G[c] = __builtin_fmaf(wk, __uint_as_float(q), G[c]);
-                        } else {
-                            // bf16 is the upper half of fp32: widening is a shift or a mask, exact
-                            G[2 * c] = __builtin_fmaf(wk, __uint_as_float(q << 16), G[2 * c]);
-                            G[2 * c + 1] =
-                                __builtin_fmaf(wk, __uint_as_float(q & 0xffff0000u), G[2 * c + 1]);
-                        }
-                    }
+                    for (int c = 0; c < VEC; ++c)
+                        __builtin_amdgcn_raw_buffer_store_b32(
+                            __float_as_uint(Ge[c]), r,
+                            off[c] == kMasked ? kMasked : (off[c] / Sh::kSize) * 4, 0, 0);
                 }
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) A = __builtin_fmaf(G[c], G[c], A);
+                for (int k0 = 0; k0 < K; k0 += CH) {
+                    if (k0 > 0) asm volatile("" : "+v"(off[0]) : "v"(n[k0 - 1]), "v"(d[k0 - 1]));
+                    wvec xe[CH];
+#pragma unroll
+                    for (int j = 0; j < CH; ++j)
+                        if (k0 + j < K) xe[j] = edge_load(k0 + j, v0, off);
+#pragma unroll
+                    for (int j = 0; j < CH; ++j)
+                        if (k0 + j < K) pass2(xe[j], Ge, k0 + j);
+                }
+            }
+        };
 
-                if (want_agg) {
-                    if (interior) {
+        int64_t v0 = pc.v_begin;
+        while (v0 < pc.v_end && !interior(v0)) {   // leading edge (at most one tile unless the
+            edge_tile(v0);                         // piece has no interior tile at all)
+            v0 += pc.v_step;
+        }
+
+        if (interior(v0)) {
+            // ---- the run of interior tiles: the hot loop
+            const bool long_run = pc.v_end - v0 > 8 * TILE;   // staggering pays only then
+            if (long_run) stagger_waves(tid);
+            // The K vectors of every lane.  A tile is always loaded one iteration ahead: by
+            // pass 2 of the tile before it, or here for the first one.
+            wvec x[U][K];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int k = 0; k < K; ++k)
+                    x[u][k] = Wd::template load<kLoadPolicy>(
+                        tile_rsrc(a.g[k], v0 * VB, kBlock * U * VB), (u * kBlock + tid) * VB);
+            int staged = 0;            // tiles parked in LDS
+            int64_t v_staged = v0;     // first of them
+            bool more = true;
+            while (more) {
+                // Software pipeline without extra registers: as pass 2 finishes with a worker's
+                // vector, the same registers take that worker's vector of the next tile, so
+                // loads are issued all through the arithmetic.  After the last interior tile
+                // the descriptor gets zero length and the loads touch no memory.
+                const int64_t vn = v0 + pc.v_step;
+                more = interior(vn);
+                const int next_bytes = more ? kBlock * U * VB : 0;
+
+                float G[U][VEC];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    pass1(x[u], G[u]);
+                    if (want_agg) {
                         // park G; every thread later reads back only what it wrote itself
 #pragma unroll
                         for (int h = 0; h < Q; ++h) {
                             wvec q;
 #pragma unroll
-                            for (int c = 0; c < LW; ++c) q[c] = __float_as_uint(G[LW * h + c]);
+                            for (int c = 0; c < LW; ++c) q[c] = __float_as_uint(G[u][LW * h + c]);
                             stage[(staged * U + u) * Q + h][tid] = q;
                         }
-                    } else {
-                        const __amdgpu_buffer_rsrc_t r =
-                            tile_rsrc(a.out_agg, v0 * (VEC * 4), kBlock * U * VEC * 4);
-                        const int o = (u * kBlock + tid) * (VEC * 4);
-                        const int64_t v = v0 + (u * kBlock + tid);
-#pragma unroll
-                        for (int c = 0; c < VEC; ++c) {
-                            const int64_t e = v * VEC + c;
-                            const int oc = (e >= pc.e_lo && e < pc.e_hi) ? o + 4 * c : kMasked;
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(G[c]), r, oc, 0, 0);
-                        }
                     }
                 }
 
-                // pass 2 over the same registers: squared norms and squared deviations
+                // Flush point: pass 1 has consumed every load of this tile and pass 2 has not
+                // yet issued any for the next one, so once all waves are here the block has no
+                // load in flight.  The parked tiles are written out and the stores waited for.
+                if (want_agg) {
+                    if (staged == 0) v_staged = v0;
+                    ++staged;
+                    if (staged == NB || !more) {
+                        __syncthreads();
+                        for (int j = 0; j < staged; ++j) {
+                            const int64_t vj = v_staged + j * pc.v_step;
+                            const __amdgpu_buffer_rsrc_t r =
+                                tile_rsrc(a.out_agg, vj * (VEC * 4), kBlock * U * VEC * 4);
 #pragma unroll
-                for (int k = 0; k < K; ++k) {
+                            for (int u = 0; u < U; ++u)
 #pragma unroll
-                    for (int c = 0; c < LW; ++c) {
-                        uint32_t q = x[u][k][c];
-                        if constexpr (DT == kF32) {
-                            const float g = __uint_as_float(q);
-                            n[k] = __builtin_fmaf(g, g, n[k]);
-                            const float t = g - G[c];
-                            d[k] = __builtin_fmaf(t, t, d[k]);
-                        } else {
-                            // keep the packed pair live and widen it again here: without this
-                            // the compiler holds all 8K widened values and halves the occupancy
-                            asm volatile("" : "+v"(q));
-                            const float g0 = __uint_as_float(q << 16);
-                            const float g1 = __uint_as_float(q & 0xffff0000u);
-                            n[k] = __builtin_fmaf(g0, g0, n[k]);
-                            n[k] = __builtin_fmaf(g1, g1, n[k]);
-                            const float t0 = g0 - G[2 * c], t1 = g1 - G[2 * c + 1];
-                            d[k] = __builtin_fmaf(t0, t0, d[k]);
-                            d[k] = __builtin_fmaf(t1, t1, d[k]);
+                                for (int h = 0; h < Q; ++h)
+                                    Wd::template store<kStorePolicy>(
+                                        stage[(j * U + u) * Q + h][tid], r,
+                                        (u * kBlock + tid) * (VEC * 4) + VB * h);
                         }
+                        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                        __syncthreads();
+                        staged = 0;
+                        if (long_run) stagger_waves(tid);
                     }
-                    // order the load after the last use of the registers it overwrites (the empty
-                    // asm ties its address to this worker's updated sums), or the scheduler
-                    // hoists all K loads and the live ranges double
-                    int pf_off = (u * kBlock + tid) * VB;
-                    asm volatile("" : "+v"(pf_off) : "v"(n[k]), "v"(d[k]));
-                    x[u][k] = Wd::template load<kLoadPolicy>(
-                        tile_rsrc(a.g[k], vn * VB, next_bytes), pf_off);
                 }
-            }
-            have = prefetch;
 
-            if (want_agg) {
-                staged = staged_after;
-                if (flush_now) {
-                    // flush: all waves have consumed their loads; write the parked tiles out and
-                    // wait for the stores before the next loads are issued
-                    __syncthreads();
-                    for (int j = 0; j < staged; ++j) {
-                        const int64_t vj = v_staged + j * pc.v_step;
-                        const __amdgpu_buffer_rsrc_t r =
-                            tile_rsrc(a.out_agg, vj * (VEC * 4), kBlock * U * VEC * 4);
 #pragma unroll
-                        for (int u = 0; u < U; ++u)
+                for (int u = 0; u < U; ++u) {
 #pragma unroll
-                            for (int h = 0; h < Q; ++h)
-                                Wd::template store<kStorePolicy>(
-                                    stage[(j * U + u) * Q + h][tid], r,
-                                    (u * kBlock + tid) * (VEC * 4) + VB * h);
+                    for (int k = 0; k < K; ++k) {
+                        pass2(x[u][k], G[u], k);
+                        // order the load after the last use of the registers it overwrites (the
+                        // empty asm ties its address to this worker's updated sums), or the
+                        // scheduler hoists all K loads and the live ranges double
+                        int pf_off = (u * kBlock + tid) * VB;
+                        asm volatile("" : "+v"(pf_off) : "v"(n[k]), "v"(d[k]));
+                        x[u][k] = Wd::template load<kLoadPolicy>(
+                            tile_rsrc(a.g[k], vn * VB, next_bytes), pf_off);
                     }
-                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                    __syncthreads();
-                    staged = 0;
-                    if (long_piece) stagger_waves(tid);
                 }
+                v0 = vn;
             }
+        }
+
+        while (v0 < pc.v_end) {   // trailing edge
+            edge_tile(v0);
+            v0 += pc.v_step;
         }
 
         // block reduction: DPP inside each wave (fp32), then the wave sums in fp64, fixed order
