@@ -40,6 +40,7 @@ __device__ __forceinline__ float wave_sum(float v)
 }
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kNT = 2;               // cache-policy bit "non-temporal": data is touched once
 constexpr int kLoadPolicy = kNT;     // gradient loads of interior tiles
@@ -205,8 +206,9 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                 } else {
                     const float g0 = __uint_as_float(q << 16);
                     const float g1 = __uint_as_float(q & 0xffff0000u);
-                    n[k] = __builtin_fmaf(g0, g0, n[k]);
-                    n[k] = __builtin_fmaf(g1, g1, n[k]);
+                    // both squares of the packed pair in one instruction, fp32 accumulate
+                    n[k] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q),
+                                                           __builtin_bit_cast(bf16x2, q), n[k], false);
                     const float t0 = g0 - Gu[2 * c], t1 = g1 - Gu[2 * c + 1];
                     d[k] = __builtin_fmaf(t0, t0, d[k]);
                     d[k] = __builtin_fmaf(t1, t1, d[k]);
