@@ -195,3 +195,36 @@ def test_permuting_workers_permutes_their_entries(oracle_mod):
     # a worker's own squared norm does not depend on its slot; the aggregate only to rounding
     assert np.array_equal(st2[0, HEAD:HEAD + w.K], st[0, HEAD:HEAD + w.K][perm])
     np.testing.assert_allclose(st2[0, :7], st[0, :7], rtol=1e-5)
+
+
+def test_kernel_timing_slots():
+    w = W.config("C1", device=DEV, P=200_000)
+    D.dynamix_timing_begin(2)
+    for _ in range(3):                       # the third call finds no free slot and is not timed
+        run_gpu(w)
+    assert D.dynamix_timing_count() == 2
+    for i in range(2):
+        t_stream, t_final = D.dynamix_timing_read(i)
+        assert 0.0 < t_stream < 50.0 and 0.0 < t_final < 50.0
+    with pytest.raises(D.DynamixError):
+        D.dynamix_timing_read(2)
+    D.dynamix_timing_begin(0)
+    assert D.dynamix_timing_count() == 0
+
+
+def test_many_shapes_outlive_the_plan_cache(oracle_mod):
+    # more distinct shapes than the cache keeps: the oldest plans are dropped and rebuilt
+    w = W.config("C1", device=DEV, P=40_000)
+    first = None
+    for i in range(140):
+        P = 20_000 + 7 * i
+        sub = W.Workload(name="sub", K=w.K, P=P, dtype=w.dtype, batch_sizes=w.batch_sizes,
+                         grads=[g[:P] for g in w.grads], segment_offsets=None, m=w.m,
+                         sigma=w.sigma, mu_sqnorm=w.mu_sqnorm)
+        agg, st = run_gpu(sub)
+        if i == 0:
+            first = (agg.copy(), st.copy(), sub)
+    agg, st = run_gpu(first[2])              # its plan was evicted meanwhile
+    assert np.array_equal(agg, first[0]) and np.array_equal(st, first[1])
+    ragg, rst = run_oracle(oracle_mod, first[2])
+    compare(agg, st, ragg, rst, w.batch_sizes, where="after eviction")
