@@ -123,6 +123,39 @@ int64_t dynamix_plan_describe(int32_t K, int64_t P, int32_t dtype, const int64_t
 const char* dynamix_status_string(int status);
 
 /*
+ * Aggregation over one adjustment cycle.  The paper's agent decides every k iterations on
+ * metrics aggregated over those k iterations (System Architecture; Problem Formulation, "State
+ * representation"), its state carries sigma_norm and sigma_norm^2, and its reward for adaptive
+ * optimizers carries -eta (sigma_norm^2 + sigma_norm) and, for every worker, the batch size
+ * regulariser -delta (log2 BatchSize - 5) ("Reward function design").  The paper does not say how
+ * the k iterations are combined; this library takes the arithmetic mean of every entry of the
+ * statistics record and, beside it, ratios formed from the mean sums.
+ *
+ * dynamix_cycle_accumulate: window[i] += stats[i] for i < count and window[count] += 1 (the
+ * number of iterations in the window); with first != 0 the window is overwritten instead
+ * (window := stats, counter := 1), which starts a cycle.  stats is the out_stats of an aggregate
+ * call (DEVICE, count doubles); window is DEVICE, count + 1 doubles, caller-owned.
+ *
+ * dynamix_cycle_summary: for each of the 1 + S records (R = DYNAMIX_STATS_HEAD + 2K doubles in
+ * the window, R + 4 in `summary`):
+ *   [0, R)  mean over the accumulated iterations of every entry of the record
+ *   [R+0]   pooled noise scale   mean(T) / (mean(A) - mean(T)/B)
+ *   [R+1]   pooled sigma2_norm   mean(T) / (B mean(A))
+ *   [R+2]   pooled sigma_norm    sqrt(max(0, [R+1]))
+ *   [R+3]   optimizer penalty    -eta (mean(sigma2_norm) + mean(sigma_norm))
+ * and after the last record K doubles, the regulariser -delta (log2 b_k - 5) of every worker.
+ * summary: DEVICE, dynamix_cycle_summary_count(K, S) = (1+S)(R+4) + K doubles.  batch_sizes: HOST,
+ * K entries > 0, constant over the cycle.  Both calls only enqueue work on `stream`, validate
+ * before any HIP call and return a dynamix_status.
+ */
+int     dynamix_cycle_accumulate(const double* stats, int64_t count, double* window, int32_t first,
+                                 void* stream);
+int     dynamix_cycle_summary(const double* window, int32_t K, int64_t num_segments,
+                              const int32_t* batch_sizes, double eta, double delta,
+                              double* summary, void* stream);
+int64_t dynamix_cycle_summary_count(int32_t K, int64_t num_segments);
+
+/*
  * Kernel timing (profiling aid).  dynamix_timing_begin(capacity) creates `capacity` slots of HIP
  * events (capacity 0 switches timing off and frees them).  While slots remain, every call to the
  * aggregate entry points records three events on its stream: before the streaming pass, between

@@ -57,6 +57,12 @@ def load():
     lib.dynamix_timing_read.restype = ctypes.c_int
     lib.dynamix_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_float),
                                         ctypes.POINTER(ctypes.c_float)]
+    lib.dynamix_cycle_accumulate.restype = ctypes.c_int
+    lib.dynamix_cycle_accumulate.argtypes = [vp, i64, vp, i32, vp]
+    lib.dynamix_cycle_summary.restype = ctypes.c_int
+    lib.dynamix_cycle_summary.argtypes = [vp, i32, i64, vp, ctypes.c_double, ctypes.c_double, vp, vp]
+    lib.dynamix_cycle_summary_count.restype = i64
+    lib.dynamix_cycle_summary_count.argtypes = [i32, i64]
     lib.dynamix_release_cached.restype = ctypes.c_int
     lib.dynamix_release_cached.argtypes = []
     _lib = lib
@@ -109,6 +115,46 @@ def dynamix_timing_read(index):
     if rc != DYNAMIX_OK:
         raise DynamixError(rc)
     return a.value, b.value
+
+
+def dynamix_cycle_summary_count(K, num_segments):
+    return int(load().dynamix_cycle_summary_count(int(K), int(num_segments)))
+
+
+def dynamix_cycle_accumulate(stats, window=None, first=False, stream=None):
+    """window += stats on the device (window := stats when first); returns the window tensor,
+    float64[stats.numel() + 1], whose last entry counts the iterations."""
+    import torch
+    count = stats.numel()
+    if window is None:
+        if not first:
+            raise ValueError("a window must be given unless this call starts a cycle")
+        window = torch.empty(count + 1, dtype=torch.float64, device=stats.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(stats.device)
+    rc = int(load().dynamix_cycle_accumulate(stats.data_ptr(), count, window.data_ptr(),
+                                             int(bool(first)), stream.cuda_stream))
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+    return window
+
+
+def dynamix_cycle_summary(window, K, num_segments, batch_sizes, eta, delta, summary=None,
+                          stream=None):
+    """Means, pooled ratios and reward terms of the cycle held in `window`; returns the summary
+    tensor float64[dynamix_cycle_summary_count(K, S)]."""
+    import torch
+    if summary is None:
+        summary = torch.empty(dynamix_cycle_summary_count(K, num_segments), dtype=torch.float64,
+                              device=window.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(window.device)
+    b = (ctypes.c_int32 * K)(*[int(x) for x in batch_sizes])
+    rc = int(load().dynamix_cycle_summary(window.data_ptr(), K, num_segments, b, float(eta),
+                                          float(delta), summary.data_ptr(), stream.cuda_stream))
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+    return summary
 
 
 def call_raw(grad_ptrs, batch_sizes, K, P, dtype, segment_offsets, num_segments, out_agg_ptr,

@@ -28,6 +28,7 @@ def _jobs():
                          os.path.join(OBJ, "stream_pass_%d_%d.o" % (dt, lo)),
                          ["-DDYNAMIX_INST_DT=%d" % dt, "-DDYNAMIX_INST_LO=%d" % lo]))
     jobs.append((os.path.join(CSRC, "final_reduce.hip"), os.path.join(OBJ, "final_reduce.o"), []))
+    jobs.append((os.path.join(CSRC, "cycle.hip"), os.path.join(OBJ, "cycle.o"), []))
     jobs.append((os.path.join(CSRC, "api.hip"), os.path.join(OBJ, "api.o"), []))
     return jobs
 

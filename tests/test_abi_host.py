@@ -146,3 +146,23 @@ def test_plan_describe_rejects_bad_shapes():
         D.dynamix_plan_describe(0, 10, 0)
     with pytest.raises(D.DynamixError):
         D.dynamix_plan_describe(4, 10, 0, [0, 5, 9])
+
+
+def test_cycle_entry_points_validate_on_the_host():
+    assert D.dynamix_cycle_summary_count(4, 0) == 16 + 4 + 4
+    assert D.dynamix_cycle_summary_count(32, 148) == 149 * 76 + 32
+    assert D.dynamix_cycle_summary_count(0, 0) == -1 and D.dynamix_cycle_summary_count(4, -1) == -1
+    lib = B.load()
+    i32 = ctypes.c_int32
+    b_ok, b_bad = (i32 * 2)(32, 64), (i32 * 2)(32, 0)
+    assert lib.dynamix_cycle_accumulate(None, 16, ST, 1, None) == B.DYNAMIX_ERR_NULL
+    assert lib.dynamix_cycle_accumulate(A16, 16, None, 1, None) == B.DYNAMIX_ERR_NULL
+    assert lib.dynamix_cycle_accumulate(A16, 0, ST, 1, None) == B.DYNAMIX_ERR_ARG
+    assert lib.dynamix_cycle_accumulate(A16 + 4, 16, ST, 1, None) == B.DYNAMIX_ERR_ALIGN
+    assert lib.dynamix_cycle_summary(None, 2, 0, b_ok, 1.0, 1.0, ST, None) == B.DYNAMIX_ERR_NULL
+    assert lib.dynamix_cycle_summary(A16, 2, 0, None, 1.0, 1.0, ST, None) == B.DYNAMIX_ERR_NULL
+    assert lib.dynamix_cycle_summary(A16, 2, 0, b_ok, 1.0, 1.0, None, None) == B.DYNAMIX_ERR_NULL
+    assert lib.dynamix_cycle_summary(A16, 0, 0, b_ok, 1.0, 1.0, ST, None) == B.DYNAMIX_ERR_ARG
+    assert lib.dynamix_cycle_summary(A16, 2, 0, b_bad, 1.0, 1.0, ST, None) == B.DYNAMIX_ERR_ARG
+    assert lib.dynamix_cycle_summary(A16, 2, -1, b_ok, 1.0, 1.0, ST, None) == B.DYNAMIX_ERR_SEGMENTS
+    assert lib.dynamix_cycle_summary(A16, 2, 0, b_ok, 1.0, 1.0, ST + 4, None) == B.DYNAMIX_ERR_ALIGN
