@@ -6,7 +6,9 @@ and batch size regulariser -delta (log2 BatchSize - 5)).
 
 The paper does not say how the k iterations are combined; the reading taken is the arithmetic
 mean of every entry of the statistics record over the cycle, plus "pooled" ratios formed from the
-mean sums (mean T over mean A), which is how the noise-scale literature averages before dividing.
+mean sums (mean T over mean A), which is how the noise-scale literature averages before dividing.  The reading itself has nothing
+in the paper to be checked against (parity against the paper: unpinned); its arithmetic is pinned
+against numpy.mean, single-iteration and identical-iteration cases and closed forms.
 Plain float64 numpy, one iteration after the other in call order.  Shares nothing with the HIP
 path.
 """
