@@ -114,21 +114,26 @@ void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int
         }
         L.block_first.push_back(L.grid);
     } else {
-        // every block owns one contiguous span of whole tiles; an odd tile count per span keeps
-        // neighbouring blocks from starting on the same memory channel phase
-        int64_t tiles_per_block = ceil_div(ntiles, max_grid);
-        if (tiles_per_block > 1) tiles_per_block |= 1;
-        const int64_t span = tiles_per_block * tile;
-        L.grid = (int)ceil_div(nvec, span);
+        // every block owns one contiguous span of whole tiles; the tile counts of two blocks
+        // differ by at most one
+        L.grid = (int)std::min<int64_t>(max_grid, ntiles);
+        const int64_t base = ntiles / L.grid, rem = ntiles % L.grid;
+        std::vector<int64_t> span_begin(L.grid + 1);   // first vector of every block's span
+        for (int b = 0; b <= L.grid; ++b)
+            span_begin[b] = std::min(nvec, (b * base + std::min<int64_t>(b, rem)) * tile);
+        span_begin[L.grid] = nvec;
         std::vector<int32_t> per_block(L.grid, 0);
         const int nseg = S > 0 ? S : 1;
         for (int j = 0; j < nseg; ++j) {
             const int64_t lo = S > 0 ? offsets[j] : 0, hi = S > 0 ? offsets[j + 1] : P;
             const int64_t v_lo = lo / VEC, v_hi = ceil_div(hi, VEC);
-            for (int64_t b = v_lo / span; b <= (v_hi - 1) / span; ++b) {
+            // blocks whose spans meet [v_lo, v_hi)
+            int b = (int)(std::upper_bound(span_begin.begin(), span_begin.end(), v_lo) -
+                          span_begin.begin()) - 1;
+            for (; b < L.grid && span_begin[b] < v_hi; ++b) {
                 Piece pc;
-                pc.v_begin = std::max(v_lo, b * span);
-                pc.v_end = std::min(v_hi, (b + 1) * span);
+                pc.v_begin = std::max(v_lo, span_begin[b]);
+                pc.v_end = std::min(v_hi, span_begin[b + 1]);
                 pc.v_step = tile;
                 pc.e_lo = std::max(lo, pc.v_begin * VEC);
                 pc.e_hi = std::min(hi, pc.v_end * VEC);

@@ -135,10 +135,9 @@ def test_plan_covers_every_element_once(dtype):
 
 def test_plan_for_the_headline_shape_is_balanced():
     pcs = check_cover(32, 138_000_000, 0, None, 256)
-    vec_per_piece = pcs[:, 1] - pcs[:, 0]
-    assert len(pcs) <= 256
-    assert vec_per_piece.max() <= 1.01 * (138_000_000 / 4) / len(pcs) + 512
-    assert ((vec_per_piece[:-1] // 512) % 2 == 1).all()         # odd tile count per span
+    tiles = -(-(pcs[:, 1] - pcs[:, 0]) // 512)
+    assert len(pcs) == 256                                       # one piece per compute unit
+    assert tiles.max() - tiles.min() <= 1
 
 
 def test_plan_describe_rejects_bad_shapes():
