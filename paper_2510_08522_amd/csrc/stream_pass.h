@@ -237,8 +237,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
         };
         auto edge_tile = [&](int64_t v0) {
             constexpr int CH = 8;   // workers whose loads are in flight together
-#pragma unroll 1
-            for (int u = 0; u < U; ++u) {
+            auto edge_vector = [&](int u) {
                 int off[VEC];
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) {
@@ -297,6 +296,14 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                     for (int j = 0; j < CH; ++j)
                         if (k0 + j < K) pass2(xe[j], Ge, k0 + j);
                 }
+            };
+            // the U vectors of a lane side by side when few workers leave the registers for it
+            if constexpr (U * K * (DT == kBF16 ? 2 : 1) <= 32) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) edge_vector(u);
+            } else {
+#pragma unroll 1
+                for (int u = 0; u < U; ++u) edge_vector(u);
             }
         };
 
