@@ -108,16 +108,17 @@ int64_t dynamix_stats_count(int32_t K, int64_t num_segments);
 /*
  * Diagnostic, pure host arithmetic (no HIP call, usable without a GPU): the work decomposition
  * the library uses for this shape on a device that keeps `max_blocks` blocks resident.
- * The range of vectors (what a lane loads at a time: 16 bytes up to 32 workers, 8 up to 48, 4 above)
- * is dealt to blocks as contiguous spans (or, with interleave != 0
- * and no segments, tile-by-tile round robin) and cut at segment boundaries into pieces; each
- * piece yields one partial statistics record.  Up to `capacity` pieces are written to
- * pieces_out as six int64 each: first vector, end vector, vector step per block iteration,
- * first element, end element (elements outside are masked), owning block.  Returns the number of pieces, or minus a dynamix_status.
+ * The range of vectors (what a lane loads at a time: 16 bytes up to 32 workers, 8 up to 48, 4
+ * above) is dealt to blocks as contiguous spans of equal cost and cut at segment boundaries into
+ * pieces; each piece yields one partial statistics record.  Up to `capacity` pieces are written
+ * to pieces_out as six int64 each: first vector, end vector, vectors per block iteration, first
+ * element, end element (elements of the first and last vector outside this range belong to the
+ * neighbouring segment and are masked), owning block.  Returns the number of pieces, or minus a
+ * dynamix_status.
  */
 int64_t dynamix_plan_describe(int32_t K, int64_t P, int32_t dtype, const int64_t* segment_offsets,
-                              int64_t num_segments, int64_t max_blocks, int32_t interleave,
-                              int64_t* pieces_out, int64_t capacity);
+                              int64_t num_segments, int64_t max_blocks, int64_t* pieces_out,
+                              int64_t capacity);
 
 /* Static, NUL-terminated description of a dynamix_status value. */
 const char* dynamix_status_string(int status);

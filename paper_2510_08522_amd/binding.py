@@ -49,7 +49,7 @@ def load():
     lib.dynamix_status_string.restype = ctypes.c_char_p
     lib.dynamix_status_string.argtypes = [ctypes.c_int]
     lib.dynamix_plan_describe.restype = i64
-    lib.dynamix_plan_describe.argtypes = [i32, i64, i32, vp, i64, i64, i32, vp, i64]
+    lib.dynamix_plan_describe.argtypes = [i32, i64, i32, vp, i64, i64, vp, i64]
     lib.dynamix_timing_begin.restype = ctypes.c_int
     lib.dynamix_timing_begin.argtypes = [i32]
     lib.dynamix_timing_count.restype = i32
@@ -81,19 +81,20 @@ def dynamix_release_cached():
     return int(load().dynamix_release_cached())
 
 
-def dynamix_plan_describe(K, P, dtype, segment_offsets=None, max_blocks=512, interleave=False):
+def dynamix_plan_describe(K, P, dtype, segment_offsets=None, max_blocks=256):
     """The work decomposition for a shape as an int64 array [pieces, 6]:
-    (first vector, end vector, vector step, first element, end element, block).  Host only."""
+    (first vector, end vector, vectors per iteration, first element, end element, block).
+    Host only."""
     lib = load()
     off, S = None, 0
     if segment_offsets is not None:
         S = len(segment_offsets) - 1
         off = (ctypes.c_int64 * (S + 1))(*[int(x) for x in segment_offsets])
-    n = lib.dynamix_plan_describe(K, P, dtype, off, S, max_blocks, int(interleave), None, 0)
+    n = lib.dynamix_plan_describe(K, P, dtype, off, S, max_blocks, None, 0)
     if n < 0:
         raise DynamixError(-n)
     out = np.zeros((n, 6), dtype=np.int64)
-    lib.dynamix_plan_describe(K, P, dtype, off, S, max_blocks, int(interleave),
+    lib.dynamix_plan_describe(K, P, dtype, off, S, max_blocks,
                               out.ctypes.data_as(ctypes.c_void_p), n)
     return out
 

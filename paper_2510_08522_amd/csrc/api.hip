@@ -1,6 +1,7 @@
 // C ABI of libdynamix: argument validation, the cached launch plan and the two launches.
 // Everything before "plan" runs without touching HIP, so a bad call costs nothing on the device.
 #include <algorithm>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <memory>
@@ -71,6 +72,7 @@ std::mutex g_mutex;
 std::vector<std::unique_ptr<Plan>> g_plans;
 uint64_t g_clock = 0;
 constexpr size_t kMaxPlans = 128;
+constexpr double kPieceCostBytes = 128.0 * 1024.0;  // streaming time that one more piece costs a block
 
 // Optional kernel timing: event triples (before the streaming pass, between the two kernels,
 // after the final reduction) recorded on the call's stream, one triple per call.
@@ -97,7 +99,7 @@ struct Layout {
 };
 
 void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int64_t max_grid,
-                 bool interleave, Layout& L)
+                 Layout& L)
 {
     const int VEC = vec_elems(K, dtype);
     const int64_t tile = (int64_t)kBlock * unroll_for(K);  // vectors per block iteration
@@ -105,23 +107,44 @@ void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int
     const int64_t ntiles = ceil_div(nvec, tile);
     if (max_grid < 1) max_grid = 1;
 
-    if (interleave && S == 0) {
-        // block b takes tiles b, b + grid, b + 2 grid, ...
+    {
+        // Every block owns one contiguous span of whole tiles.  A span costs its tiles plus a
+        // fixed amount per piece (pipeline start, boundary vectors, final flush, block reduction:
+        // about what 128 KB of streaming takes), and the spans are cut so that the costs are
+        // equal; without segments the tile counts of two blocks differ by at most one.
         L.grid = (int)std::min<int64_t>(max_grid, ntiles);
-        for (int b = 0; b < L.grid; ++b) {
-            L.pieces.push_back(Piece{b * tile, nvec, L.grid * tile, 0, P, b});
-            L.block_first.push_back(b);
+        const double tile_bytes = (double)tile * VEC * (dtype == kF32 ? 4 : 2) * K;
+        const double piece_cost =
+            1024.0 * env_int("DYNAMIX_PIECE_COST_KB", (int)(kPieceCostBytes / 1024.0)) / tile_bytes;  // in tiles
+        std::vector<int64_t> cuts;                                         // vectors where a new piece starts
+        for (int j = 1; j < S; ++j) cuts.push_back(offsets[j] / VEC);
+        const double total_cost = (double)ntiles + piece_cost * (double)cuts.size();
+        std::vector<int64_t> span_begin(L.grid + 1, 0);                    // first vector of every span
+        {
+            size_t c = 0;        // cuts already behind the walk
+            int64_t t = 0;       // tiles already dealt
+            for (int b = 1; b < L.grid; ++b) {
+                const double want = total_cost * b / L.grid;
+                // advance tile by tile over the cuts, in one jump between them
+                while (t < ntiles) {
+                    const double here = (double)t + piece_cost * (double)c;
+                    if (here >= want) break;
+                    const int64_t next_cut_tile = c < cuts.size() ? cuts[c] / tile : ntiles;
+                    if (next_cut_tile > t) {
+                        const int64_t need = (int64_t)std::ceil(want - here);
+                        t = std::min<int64_t>(std::min(next_cut_tile, t + std::max<int64_t>(need, 1)), ntiles);
+                    } else {
+                        ++c;     // the cut lies in the tile the walk stands on
+                    }
+                }
+                // every block keeps at least one tile and leaves one for each block after it
+                t = std::max<int64_t>(t, span_begin[b - 1] / tile + 1);
+                t = std::min<int64_t>(t, ntiles - (L.grid - b));
+                span_begin[b] = t * tile;
+                while (c < cuts.size() && cuts[c] / tile < t) ++c;
+            }
+            span_begin[L.grid] = nvec;
         }
-        L.block_first.push_back(L.grid);
-    } else {
-        // every block owns one contiguous span of whole tiles; the tile counts of two blocks
-        // differ by at most one
-        L.grid = (int)std::min<int64_t>(max_grid, ntiles);
-        const int64_t base = ntiles / L.grid, rem = ntiles % L.grid;
-        std::vector<int64_t> span_begin(L.grid + 1);   // first vector of every block's span
-        for (int b = 0; b <= L.grid; ++b)
-            span_begin[b] = std::min(nvec, (b * base + std::min<int64_t>(b, rem)) * tile);
-        span_begin[L.grid] = nvec;
         std::vector<int32_t> per_block(L.grid, 0);
         const int nseg = S > 0 ? S : 1;
         for (int j = 0; j < nseg; ++j) {
@@ -174,8 +197,7 @@ int build_plan(Plan& pl, int S, const int64_t* offsets)
     if (per_cu <= 0) return DYNAMIX_ERR_HIP;
 
     Layout L;
-    make_layout(pl.K, pl.dtype, pl.P, S, offsets, (int64_t)prop.multiProcessorCount * per_cu,
-                env_int("DYNAMIX_INTERLEAVE", 0) != 0, L);
+    make_layout(pl.K, pl.dtype, pl.P, S, offsets, (int64_t)prop.multiProcessorCount * per_cu, L);
     pl.grid = L.grid;
     pl.pieces = (int)L.pieces.size();
     pl.records = 1 + S;
@@ -382,16 +404,15 @@ const char* dynamix_status_string(int status)
 }
 
 int64_t dynamix_plan_describe(int32_t K, int64_t P, int32_t dtype, const int64_t* segment_offsets,
-                              int64_t num_segments, int64_t max_blocks, int32_t interleave,
-                              int64_t* pieces_out, int64_t capacity)
+                              int64_t num_segments, int64_t max_blocks, int64_t* pieces_out,
+                              int64_t capacity)
 {
     const int rc = dynamix::check_shape(K, P, dtype, segment_offsets, num_segments);
     if (rc != DYNAMIX_OK) return -rc;
     if (max_blocks < 1 || capacity < 0 || (capacity > 0 && !pieces_out)) return -DYNAMIX_ERR_ARG;
     try {
         dynamix::Layout L;
-        dynamix::make_layout(K, dtype, P, (int)num_segments, segment_offsets, max_blocks,
-                             interleave != 0, L);
+        dynamix::make_layout(K, dtype, P, (int)num_segments, segment_offsets, max_blocks, L);
         const int64_t n = (int64_t)L.pieces.size();
         for (int64_t i = 0; i < n && i < capacity; ++i) {
             const dynamix::Piece& pc = L.pieces[i];

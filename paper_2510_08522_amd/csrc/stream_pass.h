@@ -163,10 +163,6 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
 #pragma unroll
         for (int k = 0; k < K; ++k) n[k] = d[k] = 0.f;
 
-        // block-uniform: every element of the tile that starts at vector v lies inside the piece
-        auto interior = [&](int64_t v) {
-            return v < pc.v_end && v * VEC >= pc.e_lo && (v + TILE) * VEC <= pc.e_hi;
-        };
         // pass 1 over the K vectors of one lane: the weighted aggregate, k ascending
         auto pass1 = [&](const wvec (&xu)[K], float (&Gu)[VEC]) {
 #pragma unroll
@@ -215,128 +211,133 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                 }
             }
         };
-        // An edge tile (segment boundary at any element, ragged tail): element-wise loads and
-        // stores whose lane offset is pushed out of the descriptor's range for masked elements,
-        // which then read as zero and are not written.  Rare, so it favours few registers over
-        // speed: the tile is read twice (once per pass), eight workers at a time.
-        auto edge_load = [&](int k, int64_t v0, const int (&off)[VEC]) {
-            const __amdgpu_buffer_rsrc_t r = tile_rsrc(a.g[k], v0 * VB, kBlock * U * VB);
-            wvec xe;
-#pragma unroll
-            for (int c = 0; c < LW; ++c) {
-                if constexpr (DT == kF32) {
-                    xe[c] = __builtin_amdgcn_raw_buffer_load_b32(r, off[c], 0, 0);
-                } else {
-                    const uint32_t lo = __builtin_amdgcn_raw_buffer_load_b16(r, off[2 * c], 0, 0);
-                    const uint32_t hi =
-                        __builtin_amdgcn_raw_buffer_load_b16(r, off[2 * c + 1], 0, 0);
-                    xe[c] = (lo & 0xffffu) | (hi << 16);
-                }
-            }
-            return xe;
-        };
-        auto edge_tile = [&](int64_t v0) {
+        // A boundary vector: the one vector at the head or tail of a piece that also holds
+        // elements outside [lo, hi) (a segment edge at any element offset, or the ragged end of
+        // the gradient).  Lane 0 of wave 0 handles it with element-wise loads and stores whose
+        // offset is pushed out of the descriptor's range for masked elements, which then read as
+        // zero and are not written.  At most two per piece, so it favours few registers over
+        // speed: the vector is read twice (once per pass), eight workers at a time.
+        auto boundary_vector = [&](int64_t v, int64_t lo, int64_t hi) {
             constexpr int CH = 8;   // workers whose loads are in flight together
-            auto edge_vector = [&](int u) {
-                int off[VEC];
+            int off[VEC];
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) {
-                    const int64_t e = (v0 + (u * kBlock + tid)) * VEC + c;
-                    off[c] = (e >= pc.e_lo && e < pc.e_hi)
-                                 ? ((u * kBlock + tid) * VEC + c) * Sh::kSize
-                                 : kMasked;
+            for (int c = 0; c < VEC; ++c) {
+                const int64_t e = v * VEC + c;
+                off[c] = (tid == 0 && e >= lo && e < hi) ? c * Sh::kSize : kMasked;
+            }
+            auto load_worker = [&](int k) {
+                const __amdgpu_buffer_rsrc_t r = tile_rsrc(a.g[k], v * VB, VB);
+                wvec xe;
+#pragma unroll
+                for (int c = 0; c < LW; ++c) {
+                    if constexpr (DT == kF32) {
+                        xe[c] = __builtin_amdgcn_raw_buffer_load_b32(r, off[c], 0, 0);
+                    } else {
+                        const uint32_t l16 = __builtin_amdgcn_raw_buffer_load_b16(r, off[2 * c], 0, 0);
+                        const uint32_t h16 =
+                            __builtin_amdgcn_raw_buffer_load_b16(r, off[2 * c + 1], 0, 0);
+                        xe[c] = (l16 & 0xffffu) | (h16 << 16);
+                    }
                 }
-                float Ge[VEC];
+                return xe;
+            };
+            float Ge[VEC];
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) Ge[c] = 0.f;
+            for (int c = 0; c < VEC; ++c) Ge[c] = 0.f;
 #pragma unroll
-                for (int k0 = 0; k0 < K; k0 += CH) {
-                    // start this batch only when the one before has been consumed
-                    asm volatile("" : "+v"(off[0]) : "v"(Ge[0]));
-                    wvec xe[CH];
+            for (int k0 = 0; k0 < K; k0 += CH) {
+                // start this batch only when the one before has been consumed
+                asm volatile("" : "+v"(off[0]) : "v"(Ge[0]));
+                wvec xe[CH];
 #pragma unroll
-                    for (int j = 0; j < CH; ++j)
-                        if (k0 + j < K) xe[j] = edge_load(k0 + j, v0, off);
+                for (int j = 0; j < CH; ++j)
+                    if (k0 + j < K) xe[j] = load_worker(k0 + j);
 #pragma unroll
-                    for (int j = 0; j < CH; ++j) {
-                        if (k0 + j >= K) continue;
-                        const float wk = a.w[k0 + j];
+                for (int j = 0; j < CH; ++j) {
+                    if (k0 + j >= K) continue;
+                    const float wk = a.w[k0 + j];
 #pragma unroll
-                        for (int c = 0; c < LW; ++c) {
-                            const uint32_t q = xe[j][c];
-                            if constexpr (DT == kF32) {
-                                Ge[c] = __builtin_fmaf(wk, __uint_as_float(q), Ge[c]);
-                            } else {
-                                Ge[2 * c] = __builtin_fmaf(wk, __uint_as_float(q << 16), Ge[2 * c]);
-                                Ge[2 * c + 1] = __builtin_fmaf(
-                                    wk, __uint_as_float(q & 0xffff0000u), Ge[2 * c + 1]);
-                            }
+                    for (int c = 0; c < LW; ++c) {
+                        const uint32_t q = xe[j][c];
+                        if constexpr (DT == kF32) {
+                            Ge[c] = __builtin_fmaf(wk, __uint_as_float(q), Ge[c]);
+                        } else {
+                            Ge[2 * c] = __builtin_fmaf(wk, __uint_as_float(q << 16), Ge[2 * c]);
+                            Ge[2 * c + 1] = __builtin_fmaf(wk, __uint_as_float(q & 0xffff0000u),
+                                                           Ge[2 * c + 1]);
                         }
                     }
                 }
+            }
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) A = __builtin_fmaf(Ge[c], Ge[c], A);
-                if (want_agg) {
-                    const __amdgpu_buffer_rsrc_t r =
-                        tile_rsrc(a.out_agg, v0 * (VEC * 4), kBlock * U * VEC * 4);
+            for (int c = 0; c < VEC; ++c) A = __builtin_fmaf(Ge[c], Ge[c], A);
+            if (want_agg) {
+                const __amdgpu_buffer_rsrc_t r = tile_rsrc(a.out_agg, v * (VEC * 4), VEC * 4);
 #pragma unroll
-                    for (int c = 0; c < VEC; ++c)
-                        __builtin_amdgcn_raw_buffer_store_b32(
-                            __float_as_uint(Ge[c]), r,
-                            off[c] == kMasked ? kMasked : (off[c] / Sh::kSize) * 4, 0, 0);
-                }
+                for (int c = 0; c < VEC; ++c)
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(Ge[c]), r,
+                                                          off[c] == kMasked ? kMasked : c * 4, 0, 0);
+            }
 #pragma unroll
-                for (int k0 = 0; k0 < K; k0 += CH) {
-                    if (k0 > 0) asm volatile("" : "+v"(off[0]) : "v"(n[k0 - 1]), "v"(d[k0 - 1]));
-                    wvec xe[CH];
+            for (int k0 = 0; k0 < K; k0 += CH) {
+                if (k0 > 0) asm volatile("" : "+v"(off[0]) : "v"(n[k0 - 1]), "v"(d[k0 - 1]));
+                wvec xe[CH];
 #pragma unroll
-                    for (int j = 0; j < CH; ++j)
-                        if (k0 + j < K) xe[j] = edge_load(k0 + j, v0, off);
+                for (int j = 0; j < CH; ++j)
+                    if (k0 + j < K) xe[j] = load_worker(k0 + j);
 #pragma unroll
-                    for (int j = 0; j < CH; ++j)
-                        if (k0 + j < K) pass2(xe[j], Ge, k0 + j);
-                }
-            };
-            // the U vectors of a lane side by side when few workers leave the registers for it
-            if constexpr (U * K * (DT == kBF16 ? 2 : 1) <= 32) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) edge_vector(u);
-            } else {
-#pragma unroll 1
-                for (int u = 0; u < U; ++u) edge_vector(u);
+                for (int j = 0; j < CH; ++j)
+                    if (k0 + j < K) pass2(xe[j], Ge, k0 + j);
             }
         };
 
-        int64_t v0 = pc.v_begin;
-        while (v0 < pc.v_end && !interior(v0)) {   // leading edge (at most one tile unless the
-            edge_tile(v0);                         // piece has no interior tile at all)
-            v0 += pc.v_step;
+        // The piece is: an optional boundary vector at its head, a body of whole vectors
+        // [body_begin, body_end), an optional boundary vector at its tail.
+        int64_t body_begin = pc.v_begin, body_end = pc.v_end;
+        const bool head_cut = pc.e_lo > pc.v_begin * VEC;
+        const bool tail_cut = pc.e_hi < pc.v_end * VEC;
+        if (head_cut) ++body_begin;
+        if (tail_cut && pc.v_end - 1 >= body_begin) --body_end;
+        if (tid < 64) {   // wave 0 only
+            if (head_cut)
+                boundary_vector(pc.v_begin, pc.e_lo, min(pc.e_hi, (pc.v_begin + 1) * VEC));
+            if (tail_cut && pc.v_end - 1 >= body_begin)
+                boundary_vector(pc.v_end - 1, (pc.v_end - 1) * VEC, pc.e_hi);
         }
 
-        if (interior(v0)) {
-            // ---- the run of interior tiles: the hot loop
-            const bool long_run = pc.v_end - v0 > 8 * TILE;   // staggering pays only then
+        if (body_begin < body_end) {
+            // ---- the body: the hot loop.  A tile is kBlock * U vectors; the last one may be
+            // shorter, in which case its descriptors are shorter and the lanes beyond read zero
+            // and write nothing.
+            int64_t v0 = body_begin;
+            auto tile_vectors = [&](int64_t v) {
+                return v < body_end ? (int)min((int64_t)TILE, body_end - v) : 0;
+            };
+            const bool long_run = body_end - v0 > 8 * TILE;   // staggering pays only then
             if (long_run) stagger_waves(tid);
             // The K vectors of every lane.  A tile is always loaded one iteration ahead: by
             // pass 2 of the tile before it, or here for the first one.
             wvec x[U][K];
+            {
+                const int bytes = tile_vectors(v0) * VB;
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+                for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int k = 0; k < K; ++k)
-                    x[u][k] = Wd::template load<kLoadPolicy>(
-                        tile_rsrc(a.g[k], v0 * VB, kBlock * U * VB), (u * kBlock + tid) * VB);
+                    for (int k = 0; k < K; ++k)
+                        x[u][k] = Wd::template load<kLoadPolicy>(
+                            tile_rsrc(a.g[k], v0 * VB, bytes), (u * kBlock + tid) * VB);
+            }
             int staged = 0;            // tiles parked in LDS
             int64_t v_staged = v0;     // first of them
             bool more = true;
             while (more) {
                 // Software pipeline without extra registers: as pass 2 finishes with a worker's
                 // vector, the same registers take that worker's vector of the next tile, so
-                // loads are issued all through the arithmetic.  After the last interior tile
-                // the descriptor gets zero length and the loads touch no memory.
-                const int64_t vn = v0 + pc.v_step;
-                more = interior(vn);
-                const int next_bytes = more ? kBlock * U * VB : 0;
+                // loads are issued all through the arithmetic.  After the last tile the
+                // descriptor gets zero length and the loads touch no memory.
+                const int64_t vn = v0 + TILE;
+                const int next_bytes = tile_vectors(vn) * VB;
+                more = next_bytes > 0;
 
                 float G[U][VEC];
 #pragma unroll
@@ -363,9 +364,9 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                     if (staged == NB || !more) {
                         __syncthreads();
                         for (int j = 0; j < staged; ++j) {
-                            const int64_t vj = v_staged + j * pc.v_step;
-                            const __amdgpu_buffer_rsrc_t r =
-                                tile_rsrc(a.out_agg, vj * (VEC * 4), kBlock * U * VEC * 4);
+                            const int64_t vj = v_staged + j * TILE;
+                            const __amdgpu_buffer_rsrc_t r = tile_rsrc(
+                                a.out_agg, vj * (VEC * 4), tile_vectors(vj) * (VEC * 4));
 #pragma unroll
                             for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -397,11 +398,6 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                 }
                 v0 = vn;
             }
-        }
-
-        while (v0 < pc.v_end) {   // trailing edge
-            edge_tile(v0);
-            v0 += pc.v_step;
         }
 
         // block reduction: DPP inside each wave (fp32), then the wave sums in fp64, fixed order

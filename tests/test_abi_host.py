@@ -88,27 +88,31 @@ def unroll_for(K):
     return 8 if K <= 2 else 4 if K <= 8 else 2 if K <= 16 else 1
 
 
-def check_cover(K, P, dtype, off, max_blocks, interleave=False):
-    """Replay the kernel's iteration space on the host and count how often each element is
-    touched by an unmasked lane, per record."""
+def check_cover(K, P, dtype, off, max_blocks):
+    """Replay the kernel's iteration space on the host: the body of whole vectors of every piece
+    plus its boundary vectors must touch each element exactly once."""
     vec = (1 if K > 48 else 2 if K > 32 else 4) * (1 if dtype == 0 else 2)   # elements per lane and load
     tile = 512 * unroll_for(K)                              # vectors per block iteration
-    pcs = D.dynamix_plan_describe(K, P, dtype, off, max_blocks, interleave)
+    pcs = D.dynamix_plan_describe(K, P, dtype, off, max_blocks)
     assert len(pcs) >= 1
     assert (np.diff(pcs[:, 5]) >= 0).all()                      # pieces sorted by owning block
     assert pcs[:, 5].max() < max_blocks
     assert set(pcs[:, 5].tolist()) == set(range(int(pcs[:, 5].max()) + 1))   # no idle block index
     cover = np.zeros(P, dtype=np.int32)
     for vb, ve, step, elo, ehi, _ in pcs.tolist():
-        assert 0 <= vb < ve and step >= tile and step % tile == 0
-        if interleave:      # every piece strides over the whole range, clipped to [0, P)
-            assert (elo, ehi) == (0, P) and ve * vec >= P
-        else:
-            assert vb * vec <= elo < ehi <= min(P, ve * vec)
-        for v0 in range(vb, ve, step):
-            lo, hi = max(elo, v0 * vec), min(ehi, (v0 + tile) * vec)
-            if lo < hi:
-                cover[lo:hi] += 1
+        assert 0 <= vb < ve and step == tile
+        assert vb * vec <= elo < ehi <= min(P, ve * vec)
+        assert elo < (vb + 1) * vec and ehi > (ve - 1) * vec    # only the end vectors are cut
+        body_b, body_e = vb, ve
+        head_cut, tail_cut = elo > vb * vec, ehi < ve * vec
+        if head_cut:
+            body_b += 1
+            cover[elo:min(ehi, (vb + 1) * vec)] += 1
+        if tail_cut and ve - 1 >= body_b:
+            body_e -= 1
+            cover[(ve - 1) * vec:ehi] += 1
+        if body_b < body_e:
+            cover[body_b * vec:body_e * vec] += 1
     assert (cover == 1).all()
     if off is not None:                                          # pieces never straddle a segment
         seg_of = np.searchsorted(np.asarray(off), pcs[:, 3], side="right") - 1
@@ -123,7 +127,6 @@ def test_plan_covers_every_element_once(dtype):
     for K, P, mb in [(1, 1, 512), (4, 3, 512), (4, 1_000_000, 512), (8, 1_000_003, 1024),
                      (32, 777_777, 512), (64, 300_001, 256), (16, 2_000_001, 7), (3, 65_537, 1)]:
         check_cover(K, P, dtype, None, mb)
-        check_cover(K, P, dtype, None, mb, interleave=True)
         S = int(min(P, rng.integers(1, 40)))
         cuts = np.sort(rng.choice(np.arange(1, P), size=S - 1, replace=False)) if S > 1 else []
         off = [0] + [int(c) for c in cuts] + [P]

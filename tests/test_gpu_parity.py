@@ -228,21 +228,3 @@ def test_many_shapes_outlive_the_plan_cache(oracle_mod):
     assert np.array_equal(agg, first[0]) and np.array_equal(st, first[1])
     ragg, rst = run_oracle(oracle_mod, first[2])
     compare(agg, st, ragg, rst, w.batch_sizes, where="after eviction")
-
-
-def test_round_robin_tile_order_gives_the_same_answer(oracle_mod, monkeypatch):
-    # the plan can also deal tiles to blocks round robin (a tuning switch read when a plan is
-    # built); the statistics then differ only in summation order
-    w = W.config("C2", device=DEV, P=2_000_003)
-    a1, s1 = run_gpu(w)
-    D.dynamix_release_cached()
-    monkeypatch.setenv("DYNAMIX_INTERLEAVE", "1")
-    try:
-        a2, s2 = run_gpu(w)
-    finally:
-        monkeypatch.delenv("DYNAMIX_INTERLEAVE")
-        D.dynamix_release_cached()
-    assert np.array_equal(a1, a2)
-    ragg, rst = run_oracle(oracle_mod, w)
-    compare(a2, s2, ragg, rst, w.batch_sizes, where="round robin")
-    np.testing.assert_allclose(s2, s1, rtol=1e-6)
