@@ -197,7 +197,10 @@ int build_plan(Plan& pl, int S, const int64_t* offsets)
     if (per_cu <= 0) return DYNAMIX_ERR_HIP;
 
     Layout L;
-    make_layout(pl.K, pl.dtype, pl.P, S, offsets, (int64_t)prop.multiProcessorCount * per_cu, L);
+    int64_t max_grid = (int64_t)prop.multiProcessorCount * per_cu;
+    const int cap = env_int("DYNAMIX_MAX_BLOCKS", 0);   // tuning aid: another number of blocks
+    if (cap > 0) max_grid = cap;
+    make_layout(pl.K, pl.dtype, pl.P, S, offsets, max_grid, L);
     pl.grid = L.grid;
     pl.pieces = (int)L.pieces.size();
     pl.records = 1 + S;
