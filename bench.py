@@ -69,6 +69,9 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=16_000_000,
                     help="elements per worker the CPU oracle is timed on (0: skip)")
     ap.add_argument("--cpu-threads", type=int, default=16)
+    ap.add_argument("--separate-buffers", action="store_true",
+                    help="allocate the K gradient buffers one by one instead of as K rows of one "
+                         "allocation")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 2^28 floats (1 GiB read, 1 GiB "
                          "written) three times, as the known-size reference for HBM byte counters")
@@ -86,7 +89,7 @@ def main():
     D.binding.load()                      # fails loudly if the HIP library is not built
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    w = W.config(args.workload, device=dev)
+    w = W.config(args.workload, device=dev, one_allocation=not args.separate_buffers)
     out_agg = torch.empty(w.P, dtype=torch.float32, device=dev)
     out_stats = torch.empty((1 + w.S, D.DYNAMIX_STATS_HEAD + 2 * w.K), dtype=torch.float64,
                             device=dev)
@@ -156,7 +159,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": describe(w), "K": w.K, "P": w.P, "segments": w.S,
                    "input_dtype": "bf16" if w.itemsize == 2 else "fp32",
-                   "bytes_read_per_step": read_bytes, "seed": w.seed},
+                   "bytes_read_per_step": read_bytes, "seed": w.seed,
+                   "buffers": "K allocations" if args.separate_buffers else "K rows of one allocation"},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "elements_per_s": w.K * w.P / (elapsed / args.steps),
         "total_traffic_GBps": round(algo_bytes / (elapsed / args.steps) / 1e9, 2),

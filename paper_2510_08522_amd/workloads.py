@@ -77,9 +77,18 @@ def _segment_sizes(rng, P, S, lo, hi):
 
 
 def make(K, P, dtype, batch_sizes, m, sigma, seed, device="cpu", segment_offsets=None,
-         name="custom"):
-    """Draw one workload.  sigma is a scalar, or one value per segment."""
+         name="custom", one_allocation=True):
+    """Draw one workload.  sigma is a scalar, or one value per segment.
+
+    The K buffers are independent as far as the aggregation entry point is concerned (it takes
+    K pointers).  With one_allocation they are rows of a single allocation made before anything
+    else (rows padded to a multiple of 16 bytes), otherwise K allocations made one by one; on
+    the device the former is about 5 % faster to stream (placement in physical memory)."""
     dev = torch.device(device)
+    store = None
+    if one_allocation:
+        row = (P + 7) // 8 * 8
+        store = torch.empty((K, row), dtype=dtype, device=dev)
     gen = torch.Generator(device=dev)
     gen.manual_seed(int(seed))
     b = np.asarray(batch_sizes, dtype=np.int32)
@@ -105,7 +114,11 @@ def make(K, P, dtype, batch_sizes, m, sigma, seed, device="cpu", segment_offsets
         else:
             eps.mul_(sig_el).mul_(float(1.0 / np.sqrt(float(b[k]))))
         eps.add_(mu)
-        grads.append(eps.to(dtype).contiguous())
+        if store is None:
+            grads.append(eps.to(dtype).contiguous())
+        else:
+            store[k, :P].copy_(eps)           # same rounding as .to(dtype)
+            grads.append(store[k, :P])
         del eps
     mu64 = mu.double()
     musq = [float((mu64 * mu64).sum().item())]
@@ -116,7 +129,7 @@ def make(K, P, dtype, batch_sizes, m, sigma, seed, device="cpu", segment_offsets
     del mu, mu64, sig_el
     return Workload(name=name, K=K, P=P, dtype=dtype, batch_sizes=b, grads=grads,
                     segment_offsets=off, m=float(m), sigma=sig, mu_sqnorm=np.asarray(musq),
-                    seed=int(seed))
+                    seed=int(seed), extra={"one_allocation": bool(one_allocation)})
 
 
 #: (K, P, dtype, segments) of the five named configurations
@@ -129,7 +142,7 @@ SHAPES = {
 }
 
 
-def config(name, device="cpu", P=None):
+def config(name, device="cpu", P=None, one_allocation=True):
     """One of the named configurations C1..C5.  P overrides the length (the batch sizes, the
     generator parameters and the segment structure stay those of the configuration), so that
     CPU tests can use the same recipe at a size the oracle finishes quickly."""
@@ -155,5 +168,5 @@ def config(name, device="cpu", P=None):
         off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
         sigma = np.exp(rng.uniform(np.log(1e-4), np.log(1e-1), size=S))
     w = make(K, P, dtype, np.asarray(b, dtype=np.int32), m, sigma, seed, device=device,
-             segment_offsets=off, name=name)
+             segment_offsets=off, name=name, one_allocation=one_allocation)
     return w

@@ -228,3 +228,14 @@ def test_many_shapes_outlive_the_plan_cache(oracle_mod):
     assert np.array_equal(agg, first[0]) and np.array_equal(st, first[1])
     ragg, rst = run_oracle(oracle_mod, first[2])
     compare(agg, st, ragg, rst, w.batch_sizes, where="after eviction")
+
+
+def test_buffers_allocated_one_by_one(oracle_mod):
+    # same values whether the K buffers are rows of one allocation or K allocations
+    w1 = W.config("C2", device=DEV, P=1_000_003)
+    w2 = W.config("C2", device=DEV, P=1_000_003, one_allocation=False)
+    assert all(torch.equal(a, b) for a, b in zip(w1.grads, w2.grads))
+    a1, s1 = run_gpu(w1)
+    a2, s2 = run_gpu(w2)
+    assert np.array_equal(a1, a2) and np.array_equal(s1, s2)
+    check(oracle_mod, w2, "separate allocations")
