@@ -86,7 +86,10 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
-    D.binding.load()                      # fails loudly if the HIP library is not built
+    if not os.path.exists(D.binding.LIB_PATH):   # load what is built; build only if nothing is
+        from paper_2510_08522_amd import build as _build
+        _build.build()
+    D.binding.load()                      # no fallback: raises if the library cannot be loaded
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = W.config(args.workload, device=dev, one_allocation=not args.separate_buffers)

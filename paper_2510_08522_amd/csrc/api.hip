@@ -114,8 +114,7 @@ void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int
         // equal; without segments the tile counts of two blocks differ by at most one.
         L.grid = (int)std::min<int64_t>(max_grid, ntiles);
         const double tile_bytes = (double)tile * VEC * (dtype == kF32 ? 4 : 2) * K;
-        const double piece_cost =
-            1024.0 * env_int("DYNAMIX_PIECE_COST_KB", (int)(kPieceCostBytes / 1024.0)) / tile_bytes;  // in tiles
+        const double piece_cost = kPieceCostBytes / tile_bytes;            // in tiles
         std::vector<int64_t> cuts;                                         // vectors where a new piece starts
         for (int j = 1; j < S; ++j) cuts.push_back(offsets[j] / VEC);
         const double total_cost = (double)ntiles + piece_cost * (double)cuts.size();
@@ -192,8 +191,7 @@ int build_plan(Plan& pl, int S, const int64_t* offsets)
 {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, pl.device) != hipSuccess) return DYNAMIX_ERR_HIP;
-    int per_cu = env_int("DYNAMIX_BLOCKS_PER_CU", 0);
-    if (per_cu <= 0) per_cu = stream_pass_blocks_per_cu(pl.K, pl.dtype);
+    const int per_cu = stream_pass_blocks_per_cu(pl.K, pl.dtype);
     if (per_cu <= 0) return DYNAMIX_ERR_HIP;
 
     Layout L;

@@ -10,6 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load the library that is built; only when there is none do they build it
+    from paper_2510_08522_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
 
 
 @pytest.fixture(scope="session")
