@@ -9,5 +9,6 @@ from .dynamix_oracle import (  # noqa: F401
     aggregate_stats,
     build,
     max_threads,
+    sgd_step,
     stats_count,
 )

@@ -175,6 +175,26 @@ int dynamix_oracle_aggregate_stats(const void *const *grads, const int32_t *b, i
     return 0;
 }
 
+/*
+ * The model update that follows the aggregation (Algorithm 1: "compute gradient g_i and update
+ * global model"; the paper trains with SGD and Adam and prints no update formula).  Plain
+ * stochastic gradient descent with L2 weight decay, the textbook rule:
+ *     p_i <- p_i - lr * (G_i + wd * p_i)
+ * with G from the aggregation above, evaluated in long double and rounded once to double.
+ * params: P floats (widened exactly); agg: P doubles; out: P doubles.
+ */
+int dynamix_oracle_sgd_step(const double *agg, const float *params, int64_t P, double lr,
+                            double weight_decay, double *out)
+{
+    if (!agg || !params || !out || P < 1)
+        return 1;
+    for (int64_t i = 0; i < P; ++i) {
+        acc_t p = (acc_t)params[i];
+        out[i] = (double)(p - (acc_t)lr * ((acc_t)agg[i] + (acc_t)weight_decay * p));
+    }
+    return 0;
+}
+
 int dynamix_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -48,6 +48,10 @@ def _load():
             ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
             ctypes.c_int64, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64), ctypes.c_int64,
             ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double), ctypes.c_int32]
+        lib.dynamix_oracle_sgd_step.restype = ctypes.c_int
+        lib.dynamix_oracle_sgd_step.argtypes = [
+            ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_float), ctypes.c_int64,
+            ctypes.c_double, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
         lib.dynamix_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -104,3 +108,21 @@ def aggregate_stats(grads, batch_sizes, segment_offsets=None, want_agg=True, thr
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
     return agg, stats
+
+
+def sgd_step(agg, params, lr, weight_decay=0.0):
+    """p - lr * (G + weight_decay * p) with G = agg (float64[P]) and params float32[P];
+    returns float64[P]."""
+    lib = _load()
+    agg = np.ascontiguousarray(agg, dtype=np.float64)
+    params = np.ascontiguousarray(params)
+    if params.dtype != np.float32 or params.shape != agg.shape or agg.ndim != 1:
+        raise TypeError("params must be float32 and match agg")
+    out = np.empty_like(agg)
+    rc = lib.dynamix_oracle_sgd_step(
+        agg.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+        params.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), agg.shape[0], float(lr),
+        float(weight_decay), out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return out
