@@ -101,6 +101,23 @@ int dynamix_grad_aggregate_stats_ex(const void* const* grads, const int32_t* bat
                                     const int64_t* segment_offsets, int64_t num_segments,
                                     float* out_agg, double* out_stats, void* stream);
 
+/*
+ * The same pass with the model update fused in (Algorithm 1: "compute gradient g_i and update
+ * global model"): instead of writing G, the kernel applies plain stochastic gradient descent with
+ * L2 weight decay in place,
+ *     params[i] <- params[i] - lr * (G_i + weight_decay * params[i]),
+ * which saves the write of G and the optimizer's later read of it.  params: DEVICE, P floats,
+ * 16-byte aligned, read and written; it may not overlap any gradient buffer.  lr and weight_decay
+ * are plain floats (NaN is an argument error).  Everything else, including out_stats, is as for
+ * dynamix_grad_aggregate_stats_ex; the statistics are those of the gradients and do not depend
+ * on params.  The update is evaluated in fp32 as fma(-lr, fma(weight_decay, p, G), p).
+ */
+int dynamix_grad_aggregate_stats_sgd(const void* const* grads, const int32_t* batch_sizes,
+                                     int32_t K, int64_t P, int32_t dtype,
+                                     const int64_t* segment_offsets, int64_t num_segments,
+                                     float* params, float lr, float weight_decay,
+                                     double* out_stats, void* stream);
+
 /* Doubles needed for out_stats: (1 + S) * (DYNAMIX_STATS_HEAD + 2K); S = 0 without segments.
  * Returns -1 for K outside 1..DYNAMIX_K_MAX or S < 0. */
 int64_t dynamix_stats_count(int32_t K, int64_t num_segments);

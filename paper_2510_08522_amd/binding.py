@@ -44,6 +44,9 @@ def load():
     lib.dynamix_grad_aggregate_stats.argtypes = [vp, vp, i32, i64, i32, vp, vp, vp, vp]
     lib.dynamix_grad_aggregate_stats_ex.restype = ctypes.c_int
     lib.dynamix_grad_aggregate_stats_ex.argtypes = [vp, vp, i32, i64, i32, vp, i64, vp, vp, vp]
+    lib.dynamix_grad_aggregate_stats_sgd.restype = ctypes.c_int
+    lib.dynamix_grad_aggregate_stats_sgd.argtypes = [vp, vp, i32, i64, i32, vp, i64, vp,
+                                                     ctypes.c_float, ctypes.c_float, vp, vp]
     lib.dynamix_stats_count.restype = i64
     lib.dynamix_stats_count.argtypes = [i32, i64]
     lib.dynamix_status_string.restype = ctypes.c_char_p
@@ -232,3 +235,27 @@ def dynamix_grad_aggregate_stats(grads, batch_sizes, segment_offsets=None, out_a
     if rc != DYNAMIX_OK:
         raise DynamixError(rc)
     return out_agg, out_stats
+
+
+def dynamix_grad_aggregate_stats_sgd(grads, batch_sizes, params, lr, weight_decay=0.0,
+                                     segment_offsets=None, out_stats=None, stream=None):
+    """Aggregate + statistics with the SGD step fused in: params (float32[P] device tensor) is
+    updated in place to params - lr * (G + weight_decay * params).  Returns out_stats."""
+    import torch
+    if not (params.is_cuda and params.is_contiguous() and params.dtype == torch.float32
+            and params.numel() == grads[0].numel()):
+        raise ValueError("params must be a contiguous float32 device tensor of P elements")
+    kw, _, out_stats = _marshal(grads, batch_sizes, segment_offsets, None, out_stats, stream, True)
+    lib = load()
+    K = kw["K"]
+    ptrs = (ctypes.c_void_p * K)(*kw["grad_ptrs"])
+    b = (ctypes.c_int32 * K)(*kw["batch_sizes"])
+    off = None
+    if kw["segment_offsets"] is not None:
+        off = (ctypes.c_int64 * len(kw["segment_offsets"]))(*kw["segment_offsets"])
+    rc = int(lib.dynamix_grad_aggregate_stats_sgd(
+        ptrs, b, K, kw["P"], kw["dtype"], off, kw["num_segments"], params.data_ptr(), float(lr),
+        float(weight_decay), kw["out_stats_ptr"], kw["stream_ptr"]))
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+    return out_stats

@@ -281,7 +281,8 @@ int check_shape(int32_t K, int64_t P, int32_t dtype, const int64_t* offsets, int
 }
 
 int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t P, int32_t dtype,
-        const int64_t* offsets, int64_t S, float* out_agg, double* out_stats, void* stream_v)
+        const int64_t* offsets, int64_t S, float* out_agg, double* out_stats, void* stream_v,
+        float* params = nullptr, float lr = 0.f, float weight_decay = 0.f)
 {
     // ---- validation: no HIP call before this block has passed
     if (!grads || !batch_sizes || !out_stats) return DYNAMIX_ERR_NULL;
@@ -293,7 +294,8 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     }
     for (int k = 0; k < K; ++k)
         if (reinterpret_cast<uintptr_t>(grads[k]) & 15u) return DYNAMIX_ERR_ALIGN;
-    if ((reinterpret_cast<uintptr_t>(out_agg) & 15u) || (reinterpret_cast<uintptr_t>(out_stats) & 7u))
+    if ((reinterpret_cast<uintptr_t>(out_agg) & 15u) || (reinterpret_cast<uintptr_t>(out_stats) & 7u) ||
+        (reinterpret_cast<uintptr_t>(params) & 15u))
         return DYNAMIX_ERR_ALIGN;
 
     // ---- weights: B in 64-bit integers, w_k = b_k / B rounded once to fp32
@@ -328,6 +330,9 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     sa.block_first = pl->d_block_first;
     sa.out_agg = out_agg;
     sa.partials = pl->d_partials;
+    sa.params = params;
+    sa.lr = lr;
+    sa.wd = weight_decay;
     fa.B = (double)B;
     fa.partials = pl->d_partials;
     fa.rec_range = pl->d_rec_range;
@@ -358,6 +363,24 @@ int dynamix_grad_aggregate_stats_ex(const void* const* grads, const int32_t* bat
     try {
         return dynamix::run(grads, batch_sizes, K, P, dtype, segment_offsets, num_segments, out_agg,
                             out_stats, stream);
+    } catch (const std::bad_alloc&) {
+        return DYNAMIX_ERR_NOMEM;
+    } catch (...) {
+        return DYNAMIX_ERR_HIP;
+    }
+}
+
+int dynamix_grad_aggregate_stats_sgd(const void* const* grads, const int32_t* batch_sizes,
+                                     int32_t K, int64_t P, int32_t dtype,
+                                     const int64_t* segment_offsets, int64_t num_segments,
+                                     float* params, float lr, float weight_decay,
+                                     double* out_stats, void* stream)
+{
+    if (!params) return DYNAMIX_ERR_NULL;
+    if (!(lr == lr) || !(weight_decay == weight_decay)) return DYNAMIX_ERR_ARG;   // NaN
+    try {
+        return dynamix::run(grads, batch_sizes, K, P, dtype, segment_offsets, num_segments, nullptr,
+                            out_stats, stream, params, lr, weight_decay);
     } catch (const std::bad_alloc&) {
         return DYNAMIX_ERR_NOMEM;
     } catch (...) {

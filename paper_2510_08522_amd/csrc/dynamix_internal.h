@@ -43,6 +43,8 @@ struct StreamArgs {
     const int32_t* block_first;  // [grid + 1] first piece of each block
     float* out_agg;              // may be null
     double* partials;            // [pieces][2K+1]: A, n_0..n_{K-1}, d_0..d_{K-1}
+    float* params;               // fused model update: p <- p - lr (G + wd p) in place; else null
+    float lr, wd;
 };
 
 struct FinalArgs {

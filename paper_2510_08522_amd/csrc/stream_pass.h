@@ -155,7 +155,15 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
     const int tid = threadIdx.x;
     const int p_first = a.block_first[blockIdx.x];
     const int p_last = a.block_first[blockIdx.x + 1];
-    const bool want_agg = a.out_agg != nullptr;
+    // What is written per element: the aggregate G, or, with the fused model update, the new
+    // parameter p - lr (G + wd p) over the old one; nothing in statistics-only calls.
+    const bool fused = a.params != nullptr;
+    float* const out = fused ? a.params : a.out_agg;
+    const bool want_agg = out != nullptr;
+    const float neg_lr = -a.lr, wd = a.wd;
+    auto updated = [&](float g, float p) {
+        return fused ? __builtin_fmaf(neg_lr, __builtin_fmaf(wd, p, g), p) : g;
+    };
 
     for (int p = p_first; p < p_last; ++p) {
         const Piece pc = a.pieces[p];
@@ -272,11 +280,15 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
 #pragma unroll
             for (int c = 0; c < VEC; ++c) A = __builtin_fmaf(Ge[c], Ge[c], A);
             if (want_agg) {
-                const __amdgpu_buffer_rsrc_t r = tile_rsrc(a.out_agg, v * (VEC * 4), VEC * 4);
+                const __amdgpu_buffer_rsrc_t r = tile_rsrc(out, v * (VEC * 4), VEC * 4);
 #pragma unroll
-                for (int c = 0; c < VEC; ++c)
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(Ge[c]), r,
-                                                          off[c] == kMasked ? kMasked : c * 4, 0, 0);
+                for (int c = 0; c < VEC; ++c) {
+                    const int oc = off[c] == kMasked ? kMasked : c * 4;
+                    float pc_old = 0.f;
+                    if (fused) pc_old = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, oc, 0, 0));
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(updated(Ge[c], pc_old)), r,
+                                                          oc, 0, 0);
+                }
             }
 #pragma unroll
             for (int k0 = 0; k0 < K; k0 += CH) {
@@ -318,6 +330,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
             // The K vectors of every lane.  A tile is always loaded one iteration ahead: by
             // pass 2 of the tile before it, or here for the first one.
             wvec x[U][K];
+            wvec xp[U][Q];   // the parameters of the tile (fused update only; else never read)
             {
                 const int bytes = tile_vectors(v0) * VB;
 #pragma unroll
@@ -326,6 +339,14 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                     for (int k = 0; k < K; ++k)
                         x[u][k] = Wd::template load<kLoadPolicy>(
                             tile_rsrc(a.g[k], v0 * VB, bytes), (u * kBlock + tid) * VB);
+                const __amdgpu_buffer_rsrc_t rp =
+                    tile_rsrc(a.params, v0 * (VEC * 4), fused ? tile_vectors(v0) * (VEC * 4) : 0);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int h = 0; h < Q; ++h)
+                        xp[u][h] = Wd::template load<kLoadPolicy>(
+                            rp, (u * kBlock + tid) * (VEC * 4) + VB * h);
             }
             int staged = 0;            // tiles parked in LDS
             int64_t v_staged = v0;     // first of them
@@ -349,7 +370,9 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                         for (int h = 0; h < Q; ++h) {
                             wvec q;
 #pragma unroll
-                            for (int c = 0; c < LW; ++c) q[c] = __float_as_uint(G[u][LW * h + c]);
+                            for (int c = 0; c < LW; ++c)
+                                q[c] = __float_as_uint(
+                                    updated(G[u][LW * h + c], __uint_as_float(xp[u][h][c])));
                             stage[(staged * U + u) * Q + h][tid] = q;
                         }
                     }
@@ -365,8 +388,8 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                         __syncthreads();
                         for (int j = 0; j < staged; ++j) {
                             const int64_t vj = v_staged + j * TILE;
-                            const __amdgpu_buffer_rsrc_t r = tile_rsrc(
-                                a.out_agg, vj * (VEC * 4), tile_vectors(vj) * (VEC * 4));
+                            const __amdgpu_buffer_rsrc_t r =
+                                tile_rsrc(out, vj * (VEC * 4), tile_vectors(vj) * (VEC * 4));
 #pragma unroll
                             for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -395,6 +418,16 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                         x[u][k] = Wd::template load<kLoadPolicy>(
                             tile_rsrc(a.g[k], vn * VB, next_bytes), pf_off);
                     }
+                }
+                {
+                    const __amdgpu_buffer_rsrc_t rp = tile_rsrc(
+                        a.params, vn * (VEC * 4), fused ? tile_vectors(vn) * (VEC * 4) : 0);
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+#pragma unroll
+                        for (int h = 0; h < Q; ++h)
+                            xp[u][h] = Wd::template load<kLoadPolicy>(
+                                rp, (u * kBlock + tid) * (VEC * 4) + VB * h);
                 }
                 v0 = vn;
             }
