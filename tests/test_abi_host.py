@@ -168,3 +168,20 @@ def test_cycle_entry_points_validate_on_the_host():
     assert lib.dynamix_cycle_summary(A16, 2, 0, b_bad, 1.0, 1.0, ST, None) == B.DYNAMIX_ERR_ARG
     assert lib.dynamix_cycle_summary(A16, 2, -1, b_ok, 1.0, 1.0, ST, None) == B.DYNAMIX_ERR_SEGMENTS
     assert lib.dynamix_cycle_summary(A16, 2, 0, b_ok, 1.0, 1.0, ST + 4, None) == B.DYNAMIX_ERR_ALIGN
+
+
+def test_fused_sgd_entry_validates_on_the_host():
+    lib = B.load()
+    ptrs = (ctypes.c_void_p * 2)(A16, A16 + 64)
+    b = (ctypes.c_int32 * 2)(32, 64)
+
+    def call(params, lr=0.1, wd=0.0, K=2, P=100, stats=ST):
+        return lib.dynamix_grad_aggregate_stats_sgd(ptrs, b, K, P, 0, None, 0, params, lr, wd,
+                                                    stats, None)
+    assert call(None) == B.DYNAMIX_ERR_NULL
+    assert call(A16 + 8) == B.DYNAMIX_ERR_ALIGN
+    assert call(A16, lr=float("nan")) == B.DYNAMIX_ERR_ARG
+    assert call(A16, wd=float("nan")) == B.DYNAMIX_ERR_ARG
+    assert call(A16, K=0) == B.DYNAMIX_ERR_ARG
+    assert call(A16, P=0) == B.DYNAMIX_ERR_ARG
+    assert call(A16, stats=None) == B.DYNAMIX_ERR_NULL
