@@ -239,3 +239,34 @@ def test_buffers_allocated_one_by_one(oracle_mod):
     a2, s2 = run_gpu(w2)
     assert np.array_equal(a1, a2) and np.array_equal(s1, s2)
     check(oracle_mod, w2, "separate allocations")
+
+
+def test_steady_state_call_can_be_captured_in_a_graph(oracle_mod):
+    # once its plan exists, a call only launches kernels: it can be recorded into a HIP graph and
+    # replayed; every replay is checked against an eager call on the same (changed) inputs
+    w = W.config("C1", device=DEV, P=300_001)
+    out_agg = torch.empty(w.P, dtype=torch.float32, device=DEV)
+    out_st = torch.empty((1, HEAD + 2 * w.K), dtype=torch.float64, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):           # warm-up on the capture stream builds the plan
+        D.dynamix_grad_aggregate_stats_ex(w.grads, w.batch_sizes, out_agg=out_agg,
+                                          out_stats=out_st, stream=side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        D.dynamix_grad_aggregate_stats_ex(w.grads, w.batch_sizes, out_agg=out_agg,
+                                          out_stats=out_st, stream=torch.cuda.current_stream())
+    for rep in range(3):
+        for g in w.grads:                   # new gradients in the same buffers
+            g.mul_(1.0 + 0.25 * rep).add_(1e-4 * rep)
+        torch.cuda.synchronize()
+        out_agg.zero_()
+        out_st.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        a_graph, s_graph = out_agg.cpu().numpy().copy(), out_st.cpu().numpy().copy()
+        a_eager, s_eager = run_gpu(w)
+        assert np.array_equal(a_graph, a_eager) and np.array_equal(s_graph, s_eager), rep
+    ragg, rst = run_oracle(oracle_mod, w)
+    compare(a_graph, s_graph, ragg, rst, w.batch_sizes, where="graph replay")
