@@ -83,7 +83,9 @@ enum {
  *
  * Host arrays are consumed before the call returns.  Arguments are validated before the first
  * HIP call; on any error nothing is enqueued and a dynamix_status other than DYNAMIX_OK is
- * returned.  Results are valid once the caller has synchronised `stream`.  Non-finite inputs
+ * returned.  Results are valid once the caller has synchronised `stream`.  The first call with
+ * a shape on a stream also allocates and uploads the plan; every later one only launches
+ * kernels, so it may be recorded into a HIP graph.  Non-finite inputs
  * propagate by IEEE rules.  The library keeps a small workspace per (device, stream, shape),
  * allocated on the first call with that shape and reused afterwards; two calls that share it
  * must be ordered on that stream.  For fixed inputs, shape and device the results are bitwise

@@ -270,3 +270,15 @@ def test_steady_state_call_can_be_captured_in_a_graph(oracle_mod):
         assert np.array_equal(a_graph, a_eager) and np.array_equal(s_graph, s_eager), rep
     ragg, rst = run_oracle(oracle_mod, w)
     compare(a_graph, s_graph, ragg, rst, w.batch_sizes, where="graph replay")
+
+
+def test_more_than_two_to_the_31_elements(oracle_mod):
+    # indices beyond 32 bits: two workers, 2^31 + 4099 fp32 elements each (8.6 GB per buffer)
+    P = (1 << 31) + 4099
+    w = W.make(2, P, torch.float32, [48, 200], 1e-3, 1e-2, seed=31, device=DEV)
+    agg, st = run_gpu(w)
+    ragg, rst = oracle_mod.aggregate_stats(w.host_arrays(), w.batch_sizes, threads=THREADS)
+    compare(agg, st, ragg, rst, w.batch_sizes, where="P > 2^31")
+    assert st[0, 7] == float(P)
+    # the last elements, beyond the 32-bit range, are written
+    assert np.array_equal(agg[-5:].astype(np.float32), agg[-5:]) and np.abs(agg[-5:]).max() > 0
