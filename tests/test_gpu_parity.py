@@ -282,3 +282,23 @@ def test_more_than_two_to_the_31_elements(oracle_mod):
     assert st[0, 7] == float(P)
     # the last elements, beyond the 32-bit range, are written
     assert np.array_equal(agg[-5:].astype(np.float32), agg[-5:]) and np.abs(agg[-5:]).max() > 0
+
+
+def test_two_streams_at_once():
+    # calls on different streams use different plans and workspaces and may overlap
+    w1 = W.config("C2", device=DEV, P=3_000_017)
+    w2 = W.config("C1", device=DEV, P=3_000_017)
+    ref1, ref2 = run_gpu(w1), run_gpu(w2)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    outs = []
+    for rep in range(4):
+        with torch.cuda.stream(s1):
+            o1 = D.dynamix_grad_aggregate_stats_ex(w1.grads, w1.batch_sizes, stream=s1)
+        with torch.cuda.stream(s2):
+            o2 = D.dynamix_grad_aggregate_stats_ex(w2.grads, w2.batch_sizes, stream=s2)
+        outs.append((o1, o2))
+    torch.cuda.synchronize()
+    for o1, o2 in outs:
+        assert np.array_equal(o1[0].cpu().numpy(), ref1[0]) and np.array_equal(o1[1].cpu().numpy(), ref1[1])
+        assert np.array_equal(o2[0].cpu().numpy(), ref2[0]) and np.array_equal(o2[1].cpu().numpy(), ref2[1])
