@@ -148,7 +148,7 @@ def main():
     traffic = m["bytes"] if m and m["kernel"] == kernel_source_hash() else None
 
     line = {
-        "metric": "gradient GB/s processed (aggregate+stats)",
+        "metric": "gradient GB/s processed (aggregate+stats) and % of MI355X HBM peak",
         "value": round(value, 2),
         "unit": "GB/s",
         "n_gpus": 1,
