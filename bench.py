@@ -54,10 +54,20 @@ def cpu_baseline(w, sample_elems, threads):
     oracle.aggregate_stats(host, w.batch_sizes, off, want_agg=True, threads=threads)
     dt = time.perf_counter() - t0
     nbytes = w.K * n * w.itemsize
+    # the same oracle on one thread, on a sixteenth of that sample
+    n1 = max(1, n // 16)
+    off1 = None if off is None else [o for o in off if o < n1] + [n1]
+    host1 = [h[:n1] for h in host]
+    t0 = time.perf_counter()
+    oracle.aggregate_stats(host1, w.batch_sizes, off1, want_agg=True, threads=1)
+    dt1 = time.perf_counter() - t0
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": "first %d of %d elements of each of the %d worker buffers "
                       "(%.3f GB read, %.2f s wall)" % (n, w.P, w.K, nbytes / 1e9, dt),
-            "elements_per_s": w.K * n / dt}
+            "elements_per_s": w.K * n / dt,
+            "single_thread": {"value": w.K * n1 * w.itemsize / dt1 / 1e9, "unit": "GB/s",
+                              "sample": "first %d elements of each buffer, %.2f s wall"
+                                        % (n1, dt1)}}
 
 
 def main():
@@ -72,6 +82,10 @@ def main():
     ap.add_argument("--separate-buffers", action="store_true",
                     help="allocate the K gradient buffers one by one instead of as K rows of one "
                          "allocation")
+    ap.add_argument("--warm", action="store_true",
+                    help="time one input set over and over even when it fits the 256 MB "
+                         "memory-side cache (default: rotate copies of it so every step reads "
+                         "from HBM)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 2^28 floats (1 GiB read, 1 GiB "
                          "written) three times, as the known-size reference for HBM byte counters")
@@ -98,9 +112,28 @@ def main():
                             device=dev)
     stream = torch.cuda.current_stream()
 
+    # Cold-cache protocol: a workload that the 256 MB memory-side cache could hold between steps
+    # is timed on a rotation of copies at distinct addresses, together more than twice the cache.
+    CACHE = 256 << 20
+    sets = [(w.grads, out_agg)]
+    if w.bytes_read + w.P * 4 > 2 * CACHE:
+        cache_note = "cold by size: one step streams %.0f MB through a 256 MB cache" % (
+            (w.bytes_read + w.P * 4) / 1e6)
+    elif args.warm:
+        cache_note = "warm: the same %.0f MB every step" % (w.bytes_read / 1e6)
+    else:
+        copies = -(-(5 * CACHE // 2) // (w.bytes_read + w.P * 4))
+        for _ in range(copies - 1):
+            sets.append(([g.clone() for g in w.grads], torch.empty_like(out_agg)))
+        cache_note = "cold: rotation of %d copies of the inputs at distinct addresses (%.0f MB)" % (
+            copies, copies * (w.bytes_read + w.P * 4) / 1e6)
+    calls = [0]
+
     def step():
-        D.dynamix_grad_aggregate_stats_ex(w.grads, w.batch_sizes, w.segment_offsets,
-                                          out_agg=out_agg, out_stats=out_stats, stream=stream)
+        grads, agg = sets[calls[0] % len(sets)]
+        calls[0] += 1
+        D.dynamix_grad_aggregate_stats_ex(grads, w.batch_sizes, w.segment_offsets,
+                                          out_agg=agg, out_stats=out_stats, stream=stream)
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -129,8 +162,10 @@ def main():
     so_steps = min(args.steps, 20)
     D.dynamix_timing_begin(so_steps)
     for _ in range(so_steps):
-        D.dynamix_grad_aggregate_stats_ex(w.grads, w.batch_sizes, w.segment_offsets,
-                                          out_stats=out_stats, stream=stream, stats_only=True)
+        D.dynamix_grad_aggregate_stats_ex(sets[calls[0] % len(sets)][0], w.batch_sizes,
+                                          w.segment_offsets, out_stats=out_stats, stream=stream,
+                                          stats_only=True)
+        calls[0] += 1
     torch.cuda.synchronize()
     so_ms = sum(D.dynamix_timing_read(i)[0] for i in range(so_steps)) / so_steps
     D.dynamix_timing_begin(0)
@@ -163,7 +198,8 @@ def main():
         "config": {"workload": describe(w), "K": w.K, "P": w.P, "segments": w.S,
                    "input_dtype": "bf16" if w.itemsize == 2 else "fp32",
                    "bytes_read_per_step": read_bytes, "seed": w.seed,
-                   "buffers": "K allocations" if args.separate_buffers else "K rows of one allocation"},
+                   "buffers": "K allocations" if args.separate_buffers else "K rows of one allocation",
+                   "cache": cache_note},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "elements_per_s": w.K * w.P / (elapsed / args.steps),
         "total_traffic_GBps": round(algo_bytes / (elapsed / args.steps) / 1e9, 2),
