@@ -11,4 +11,5 @@ from .dynamix_oracle import (  # noqa: F401
     max_threads,
     sgd_step,
     stats_count,
+    widen,
 )

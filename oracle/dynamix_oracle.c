@@ -34,7 +34,7 @@
  * vector, records 1..S are the caller's contiguous segments (layers).  The global record is
  * summed directly over [0, P), never by adding segment records.
  *
- * Arithmetic: inputs are widened exactly (fp32 and bf16 are subsets of double); every sum over
+ * Arithmetic: inputs are widened exactly (fp32, bf16 and fp16 are subsets of double); every sum over
  * i is carried in an x87 80-bit long double accumulator, so the oracle's own rounding error is
  * ~1e-16 relative even over 1e8 terms.  No blocking, no fusion: one loop over i, an inner loop
  * over k.  With threads > 1 the index range is cut into `threads` equal consecutive blocks, each
@@ -56,18 +56,42 @@
 
 typedef long double acc_t;
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 enum { ORACLE_HEAD = 8 }; /* scalars in front of the per-worker entries of a record */
 
 static inline double widen(const void *base, int dtype, int64_t i)
 {
     if (dtype == ORACLE_F32)
         return (double)((const float *)base)[i];
+    if (dtype == ORACLE_F16) {
+        /* IEEE 754 binary16 decoded field by field: 1 sign, 5 exponent (bias 15), 10 fraction */
+        uint16_t h = ((const uint16_t *)base)[i];
+        int e = (h >> 10) & 0x1f;
+        int m = h & 0x3ff;
+        double v;
+        if (e == 0)
+            v = ldexp((double)m, -24);               /* zero and subnormals: m * 2^-24 */
+        else if (e == 31)
+            v = m ? (double)NAN : (double)INFINITY;
+        else
+            v = ldexp((double)(1024 + m), e - 25);   /* (1 + m/1024) * 2^(e-15) */
+        return (h & 0x8000) ? -v : v;
+    }
     /* bf16 is the upper half of the fp32 encoding */
     uint32_t bits = (uint32_t)((const uint16_t *)base)[i] << 16;
     float f;
     memcpy(&f, &bits, sizeof f);
     return (double)f;
+}
+
+/* The exact value of each of n stored elements as a double (what every sum below starts from). */
+int dynamix_oracle_widen(const void *base, int32_t dtype, int64_t n, double *out)
+{
+    if (!base || !out || n < 0 || dtype < ORACLE_F32 || dtype > ORACLE_F16)
+        return 1;
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = widen(base, dtype, i);
+    return 0;
 }
 
 /* raw sums of one consecutive block: sums[0]=A, sums[1..K]=n_k, sums[1+K..2K]=d_k */
@@ -141,7 +165,8 @@ static int record(const void *const *g, const int32_t *b, int K, int dtype, int6
 }
 
 /*
- * grads: K host pointers, each P elements of dtype (0 = fp32, 1 = bf16 as uint16).
+ * grads: K host pointers, each P elements of dtype (0 = fp32, 1 = bf16 as uint16, 2 = fp16 as
+ * uint16).
  * b: K positive batch sizes.  offsets: S+1 strictly increasing entries, offsets[0] == 0,
  * offsets[S] == P, or NULL with S == 0 (global record only).
  * agg: P doubles or NULL.  stats: (1+S) * (8+2K) doubles.
@@ -151,7 +176,7 @@ int dynamix_oracle_aggregate_stats(const void *const *grads, const int32_t *b, i
                                    int64_t P, int32_t dtype, const int64_t *offsets, int64_t S,
                                    double *agg, double *stats, int32_t threads)
 {
-    if (!grads || !b || !stats || K < 1 || P < 1 || (dtype != ORACLE_F32 && dtype != ORACLE_BF16))
+    if (!grads || !b || !stats || K < 1 || P < 1 || dtype < ORACLE_F32 || dtype > ORACLE_F16)
         return 1;
     for (int k = 0; k < K; ++k)
         if (!grads[k] || b[k] <= 0)

@@ -53,12 +53,26 @@ def _load():
             ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_float), ctypes.c_int64,
             ctypes.c_double, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
         lib.dynamix_oracle_max_threads.restype = ctypes.c_int
+        lib.dynamix_oracle_widen.restype = ctypes.c_int
+        lib.dynamix_oracle_widen.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64,
+                                             ctypes.c_void_p]
         _lib = lib
     return _lib
 
 
 def max_threads():
     return int(_load().dynamix_oracle_max_threads())
+
+
+def widen(stored):
+    """The value the oracle takes each stored element to be, as float64: `stored` is a 1-d array
+    of float32, float16, or uint16 holding bf16 bit patterns."""
+    a = np.ascontiguousarray(stored)
+    code = {np.dtype(np.float32): 0, np.dtype(np.uint16): 1, np.dtype(np.float16): 2}[a.dtype]
+    out = np.empty(a.shape[0], dtype=np.float64)
+    if _load().dynamix_oracle_widen(a.ctypes.data, code, a.shape[0], out.ctypes.data) != 0:
+        raise ValueError("oracle rejected the arguments")
+    return out
 
 
 def stats_count(K, S):
@@ -68,8 +82,8 @@ def stats_count(K, S):
 def aggregate_stats(grads, batch_sizes, segment_offsets=None, want_agg=True, threads=1):
     """Run the oracle.
 
-    grads: K one-dimensional numpy arrays of equal length, dtype float32, or uint16 holding
-    bf16 bit patterns.  batch_sizes: K positive integers.  segment_offsets: None, or S+1
+    grads: K one-dimensional numpy arrays of equal length, dtype float32, float16, or uint16
+    holding bf16 bit patterns.  batch_sizes: K positive integers.  segment_offsets: None, or S+1
     increasing offsets from 0 to P.
     Returns (agg, stats): agg is float64[P] (None if not wanted), stats is float64[1+S, 8+2K].
     """
@@ -83,8 +97,10 @@ def aggregate_stats(grads, batch_sizes, segment_offsets=None, want_agg=True, thr
         code = 0
     elif dt == np.uint16:
         code = 1
+    elif dt == np.float16:
+        code = 2
     else:
-        raise TypeError("gradients must be float32 or uint16 (bf16 bits), got %s" % dt)
+        raise TypeError("gradients must be float32, float16 or uint16 (bf16 bits), got %s" % dt)
     P = arrs[0].shape[0]
     for a in arrs:
         if a.ndim != 1 or a.shape[0] != P or a.dtype != dt:

@@ -14,7 +14,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import HEAD, IDX, aggregate_stats
+from oracle import HEAD, IDX, aggregate_stats, widen
 from oracle.bruteforce import exact_record
 from paper_2510_08522_amd import workloads as W
 
@@ -175,7 +175,22 @@ def test_batch_size_scaling_leaves_mean_unchanged():
 
 
 # ---------------------------------------------------------------- exact brute force, tiny P
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_widening_of_every_16_bit_pattern():
+    """The oracle's value of every fp16 and bf16 bit pattern against the conversions of numpy
+    (binary16) and torch (bfloat16), which share no code with it."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    for got, ref in [(widen(bits.view(np.float16)), bits.view(np.float16).astype(np.float64)),
+                     (widen(bits), torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16)
+                      .to(torch.float64).numpy())]:
+        nan = np.isnan(ref)
+        assert (np.isnan(got) == nan).all()
+        assert (got[~nan] == ref[~nan]).all()
+        assert (np.signbit(got[~nan]) == np.signbit(ref[~nan])).all()     # -0.0 stays -0.0
+    x = np.random.default_rng(1).standard_normal(1000).astype(np.float32)
+    assert (widen(x) == x.astype(np.float64)).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("K,P,threads", [(1, 5, 1), (2, 1, 1), (3, 64, 1), (5, 37, 3), (8, 64, 4)])
 def test_bruteforce_exact_rationals(dtype, K, P, threads):
     rng = np.random.default_rng(100 + K * 64 + P)
@@ -184,6 +199,10 @@ def test_bruteforce_exact_rationals(dtype, K, P, threads):
     if dtype == "bf16":
         g = [to_bf16_bits(x) for x in g32]
         vals = [bf16_bits_to_f64(x) for x in g]
+    elif dtype == "f16":
+        g = [x.astype(np.float16) for x in g32]
+        g[0][::7] = np.float16(3e-6)                       # a few subnormals
+        vals = [x.astype(np.float64) for x in g]
     else:
         g = g32
         vals = [x.astype(np.float64) for x in g]
