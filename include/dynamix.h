@@ -31,9 +31,14 @@
 extern "C" {
 #endif
 
-/* Storage type of the gradient buffers.  Accumulation is fp32 per lane and fp64 across blocks
- * for both; the aggregate is always written as fp32. */
-typedef enum { DYNAMIX_F32 = 0, DYNAMIX_BF16 = 1 } dynamix_dtype;
+/* Storage type of the gradient buffers.  Every stored value is widened exactly (fp16
+ * subnormals included); accumulation is fp32 per lane and fp64 across blocks for all three; the
+ * aggregate is always written as fp32.
+ * Non-finite inputs propagate per IEEE 754 and are not trapped: an Inf or NaN in worker k's
+ * buffer makes worker_sqnorm[k] (and only that worker's) non-finite, which serves as the
+ * overflow flag of loss-scaled fp16 training; the aggregate, its norm and all deviations are
+ * then non-finite too in the records that cover the element. */
+typedef enum { DYNAMIX_F32 = 0, DYNAMIX_BF16 = 1, DYNAMIX_F16 = 2 } dynamix_dtype;
 
 typedef enum {
     DYNAMIX_OK = 0,

@@ -12,7 +12,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdynamix.so")
 
-DYNAMIX_F32, DYNAMIX_BF16 = 0, 1
+DYNAMIX_F32, DYNAMIX_BF16, DYNAMIX_F16 = 0, 1, 2
 DYNAMIX_OK = 0
 DYNAMIX_ERR_NULL, DYNAMIX_ERR_ARG, DYNAMIX_ERR_SEGMENTS = 1, 2, 3
 DYNAMIX_ERR_ALIGN, DYNAMIX_ERR_NOMEM, DYNAMIX_ERR_HIP = 4, 5, 6
@@ -186,8 +186,10 @@ def _marshal(grads, batch_sizes, segment_offsets, out_agg, out_stats, stream, st
         dtype = DYNAMIX_F32
     elif g0.dtype == torch.bfloat16:
         dtype = DYNAMIX_BF16
+    elif g0.dtype == torch.float16:
+        dtype = DYNAMIX_F16
     else:
-        raise TypeError("gradients must be float32 or bfloat16")
+        raise TypeError("gradients must be float32, bfloat16 or float16")
     P = g0.numel()
     for g in grads:
         if not (g.is_cuda and g.is_contiguous() and g.dim() == 1 and g.numel() == P
@@ -213,7 +215,7 @@ def dynamix_grad_aggregate_stats_ex(grads, batch_sizes, segment_offsets=None, ou
                                     out_stats=None, stream=None, stats_only=False):
     """Enqueue one aggregate + statistics pass on `stream` (default: torch's current stream).
 
-    grads: K contiguous 1-d device tensors (float32 or bfloat16).  Returns (out_agg, out_stats):
+    grads: K contiguous 1-d device tensors (float32, bfloat16 or float16).  Returns (out_agg, out_stats):
     float32[P] (None when stats_only) and float64[1+S, 8+2K]; valid after the stream is
     synchronised.  Raises DynamixError on a non-zero status.
     """

@@ -1,7 +1,7 @@
 """Builds libdynamix.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
 
-The streaming pass is instantiated for every K in 1..64 and both storage types; the
-instantiations are split over sixteen translation units that compile in parallel.
+The streaming pass is instantiated for every K in 1..64 and the three storage types; the
+instantiations are split over 24 translation units that compile in parallel.
 Run as `python -m paper_2510_08522_amd.build`.
 """
 import os
@@ -22,7 +22,7 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-u
 
 def _jobs():
     jobs = []
-    for dt in (0, 1):
+    for dt in (0, 1, 2):
         for lo in range(1, 65, 8):
             jobs.append((os.path.join(CSRC, "stream_pass_inst.hip"),
                          os.path.join(OBJ, "stream_pass_%d_%d.o" % (dt, lo)),

@@ -18,23 +18,26 @@ struct Unit {
     hipError_t (*launch)(int, int, const StreamArgs&, hipStream_t);
     int (*occupancy)(int);
 };
-static const Unit kUnits[2][kKMax / 8] = {
+static const Unit kUnits[kDtypes][kKMax / 8] = {
     {DYNAMIX_UNIT_ENTRY(0, 1) DYNAMIX_UNIT_ENTRY(0, 9) DYNAMIX_UNIT_ENTRY(0, 17)
          DYNAMIX_UNIT_ENTRY(0, 25) DYNAMIX_UNIT_ENTRY(0, 33) DYNAMIX_UNIT_ENTRY(0, 41)
              DYNAMIX_UNIT_ENTRY(0, 49) DYNAMIX_UNIT_ENTRY(0, 57)},
     {DYNAMIX_UNIT_ENTRY(1, 1) DYNAMIX_UNIT_ENTRY(1, 9) DYNAMIX_UNIT_ENTRY(1, 17)
          DYNAMIX_UNIT_ENTRY(1, 25) DYNAMIX_UNIT_ENTRY(1, 33) DYNAMIX_UNIT_ENTRY(1, 41)
-             DYNAMIX_UNIT_ENTRY(1, 49) DYNAMIX_UNIT_ENTRY(1, 57)}};
+             DYNAMIX_UNIT_ENTRY(1, 49) DYNAMIX_UNIT_ENTRY(1, 57)},
+    {DYNAMIX_UNIT_ENTRY(2, 1) DYNAMIX_UNIT_ENTRY(2, 9) DYNAMIX_UNIT_ENTRY(2, 17)
+         DYNAMIX_UNIT_ENTRY(2, 25) DYNAMIX_UNIT_ENTRY(2, 33) DYNAMIX_UNIT_ENTRY(2, 41)
+             DYNAMIX_UNIT_ENTRY(2, 49) DYNAMIX_UNIT_ENTRY(2, 57)}};
 
 hipError_t launch_stream_pass(int K, int dtype, int grid, const StreamArgs& a, hipStream_t s)
 {
-    if (K < 1 || K > kKMax || (dtype != kF32 && dtype != kBF16)) return hipErrorInvalidValue;
+    if (K < 1 || K > kKMax || dtype < 0 || dtype >= kDtypes) return hipErrorInvalidValue;
     return kUnits[dtype][(K - 1) / 8].launch(K, grid, a, s);
 }
 
 int stream_pass_blocks_per_cu(int K, int dtype)
 {
-    if (K < 1 || K > kKMax || (dtype != kF32 && dtype != kBF16)) return 0;
+    if (K < 1 || K > kKMax || dtype < 0 || dtype >= kDtypes) return 0;
     return kUnits[dtype][(K - 1) / 8].occupancy(K);
 }
 
@@ -268,7 +271,7 @@ int get_plan(int device, hipStream_t stream, int K, int dtype, int64_t P, int S,
 
 int check_shape(int32_t K, int64_t P, int32_t dtype, const int64_t* offsets, int64_t S)
 {
-    if (K < 1 || K > kKMax || P < 1 || (dtype != DYNAMIX_F32 && dtype != DYNAMIX_BF16))
+    if (K < 1 || K > kKMax || P < 1 || dtype < DYNAMIX_F32 || dtype > DYNAMIX_F16)
         return DYNAMIX_ERR_ARG;
     if (S < 0 || S > INT32_MAX / 4) return DYNAMIX_ERR_SEGMENTS;
     if ((S == 0) != (offsets == nullptr)) return DYNAMIX_ERR_SEGMENTS;

@@ -10,7 +10,8 @@ constexpr int kBlock = 512;      // threads per block of the streaming pass: 8 w
 constexpr int kWaves = kBlock / 64;
 constexpr int kHead = 8;         // scalars in front of the per-worker entries of a record
 
-enum : int { kF32 = 0, kBF16 = 1 };
+enum : int { kF32 = 0, kBF16 = 1, kF16 = 2 };
+constexpr int kDtypes = 3;
 
 // Vectors (16-byte loads) per thread and block iteration.  Small K gets several so that each
 // lane keeps enough independent loads in flight; K x U x 4 data registers stay live until the
@@ -69,7 +70,8 @@ hipError_t launch_final_reduce(int records, const FinalArgs& a, hipStream_t s);
     int occupancy_stream_pass_##DT##_##LO(int K);
 #define DYNAMIX_FOR_EACH_UNIT(X) \
     X(0, 1) X(0, 9) X(0, 17) X(0, 25) X(0, 33) X(0, 41) X(0, 49) X(0, 57) \
-    X(1, 1) X(1, 9) X(1, 17) X(1, 25) X(1, 33) X(1, 41) X(1, 49) X(1, 57)
+    X(1, 1) X(1, 9) X(1, 17) X(1, 25) X(1, 33) X(1, 41) X(1, 49) X(1, 57) \
+    X(2, 1) X(2, 9) X(2, 17) X(2, 25) X(2, 33) X(2, 41) X(2, 49) X(2, 57)
 DYNAMIX_FOR_EACH_UNIT(DYNAMIX_DECLARE_UNIT)
 
 }  // namespace dynamix

@@ -42,13 +42,29 @@ __device__ __forceinline__ float wave_sum(float v)
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
+// The two 16-bit elements packed in a 32-bit word, widened to fp32 (exact for both formats).
+// bf16 is the upper half of the fp32 encoding, so widening is a shift or a mask; fp16 goes
+// through the hardware conversion, subnormals included.
+template <int DT>
+__device__ __forceinline__ float elem_lo(uint32_t q)
+{
+    if constexpr (DT == kBF16) return __uint_as_float(q << 16);
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)(q & 0xffffu));
+}
+template <int DT>
+__device__ __forceinline__ float elem_hi(uint32_t q)
+{
+    if constexpr (DT == kBF16) return __uint_as_float(q & 0xffff0000u);
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)(q >> 16));
+}
+
 constexpr int kNT = 2;               // cache-policy bit "non-temporal": data is touched once
 constexpr int kLoadPolicy = kNT;     // gradient loads of interior tiles
 constexpr int kStorePolicy = kNT;    // aggregate stores of interior tiles
 
 // One "vector" is what a lane loads at a time: LW 32-bit words (4 up to K = 32, then 2, then 1, so
 // that the K vectors of a lane and the 2K+1 sums still fit the register file), i.e. LW fp32 or
-// 2 LW bf16 elements.
+// 2 LW bf16 or fp16 elements.
 template <int LW>
 struct Words;
 template <>
@@ -184,10 +200,8 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                     if constexpr (DT == kF32) {
                         Gu[c] = __builtin_fmaf(wk, __uint_as_float(q), Gu[c]);
                     } else {
-                        // bf16 is the upper half of fp32: widening is a shift or a mask, exact
-                        Gu[2 * c] = __builtin_fmaf(wk, __uint_as_float(q << 16), Gu[2 * c]);
-                        Gu[2 * c + 1] =
-                            __builtin_fmaf(wk, __uint_as_float(q & 0xffff0000u), Gu[2 * c + 1]);
+                        Gu[2 * c] = __builtin_fmaf(wk, elem_lo<DT>(q), Gu[2 * c]);
+                        Gu[2 * c + 1] = __builtin_fmaf(wk, elem_hi<DT>(q), Gu[2 * c + 1]);
                     }
                 }
             }
@@ -208,11 +222,16 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                     const float t = g - Gu[c];
                     d[k] = __builtin_fmaf(t, t, d[k]);
                 } else {
-                    const float g0 = __uint_as_float(q << 16);
-                    const float g1 = __uint_as_float(q & 0xffff0000u);
-                    // both squares of the packed pair in one instruction, fp32 accumulate
-                    n[k] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q),
-                                                           __builtin_bit_cast(bf16x2, q), n[k], false);
+                    const float g0 = elem_lo<DT>(q), g1 = elem_hi<DT>(q);
+                    if constexpr (DT == kBF16) {
+                        // both squares of the packed pair in one instruction, fp32 accumulate
+                        n[k] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q),
+                                                               __builtin_bit_cast(bf16x2, q), n[k],
+                                                               false);
+                    } else {
+                        n[k] = __builtin_fmaf(g0, g0, n[k]);
+                        n[k] = __builtin_fmaf(g1, g1, n[k]);
+                    }
                     const float t0 = g0 - Gu[2 * c], t1 = g1 - Gu[2 * c + 1];
                     d[k] = __builtin_fmaf(t0, t0, d[k]);
                     d[k] = __builtin_fmaf(t1, t1, d[k]);
@@ -270,9 +289,8 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                         if constexpr (DT == kF32) {
                             Ge[c] = __builtin_fmaf(wk, __uint_as_float(q), Ge[c]);
                         } else {
-                            Ge[2 * c] = __builtin_fmaf(wk, __uint_as_float(q << 16), Ge[2 * c]);
-                            Ge[2 * c + 1] = __builtin_fmaf(wk, __uint_as_float(q & 0xffff0000u),
-                                                           Ge[2 * c + 1]);
+                            Ge[2 * c] = __builtin_fmaf(wk, elem_lo<DT>(q), Ge[2 * c]);
+                            Ge[2 * c + 1] = __builtin_fmaf(wk, elem_hi<DT>(q), Ge[2 * c + 1]);
                         }
                     }
                 }

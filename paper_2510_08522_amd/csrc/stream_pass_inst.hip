@@ -1,6 +1,6 @@
 // Instantiation unit of the streaming pass: compiled once per dtype and range of K
-// (-DDYNAMIX_INST_DT=<0|1> -DDYNAMIX_INST_LO=<first K>; eight consecutive K per unit) so that the
-// 128 kernels build in parallel.
+// (-DDYNAMIX_INST_DT=<0|1|2> -DDYNAMIX_INST_LO=<first K>; eight consecutive K per unit) so that the
+// 192 kernels build in parallel.
 #include "stream_pass.h"
 
 #ifndef DYNAMIX_INST_DT

@@ -47,7 +47,7 @@ class Workload:
 
     @property
     def itemsize(self):
-        return 2 if self.dtype == torch.bfloat16 else 4
+        return 4 if self.dtype == torch.float32 else 2
 
     @property
     def bytes_read(self):
@@ -55,7 +55,7 @@ class Workload:
 
     def host_arrays(self, lo=0, hi=None):
         """The K inputs (or the slice [lo, hi) of each) as numpy arrays the oracle accepts:
-        float32, or uint16 holding the bf16 bit patterns."""
+        float32, float16, or uint16 holding the bf16 bit patterns."""
         out = []
         for g in self.grads:
             t = g[lo:hi].detach().cpu().contiguous()

@@ -59,7 +59,8 @@ def test_validation_precedes_any_device_work():
     assert raw(ok_p, ok_b, 0, 100) == B.DYNAMIX_ERR_ARG
     assert raw([A16] * 65, [1] * 65, 65, 100) == B.DYNAMIX_ERR_ARG
     assert raw(ok_p, ok_b, 2, 0) == B.DYNAMIX_ERR_ARG
-    assert raw(ok_p, ok_b, 2, 100, dtype=2) == B.DYNAMIX_ERR_ARG
+    assert raw(ok_p, ok_b, 2, 100, dtype=3) == B.DYNAMIX_ERR_ARG
+    assert raw(ok_p, ok_b, 2, 100, dtype=-1) == B.DYNAMIX_ERR_ARG
     assert raw(ok_p, [32, 0], 2, 100) == B.DYNAMIX_ERR_ARG
     assert raw(ok_p, [32, -5], 2, 100) == B.DYNAMIX_ERR_ARG
     assert raw([A16, A16 + 4], ok_b, 2, 100) == B.DYNAMIX_ERR_ALIGN
@@ -121,7 +122,7 @@ def check_cover(K, P, dtype, off, max_blocks):
     return pcs
 
 
-@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("dtype", [0, 1, 2])
 def test_plan_covers_every_element_once(dtype):
     rng = np.random.default_rng(5)
     for K, P, mb in [(1, 1, 512), (4, 3, 512), (4, 1_000_000, 512), (8, 1_000_003, 1024),

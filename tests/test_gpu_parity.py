@@ -59,7 +59,7 @@ def test_config_c5_full_size_segments(oracle_mod):
 
 
 # ------------------------------------------------------------------ shapes: every K, ragged tails
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 @pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 24, 31, 32, 33, 48, 63, 64])
 def test_worker_counts_and_ragged_tail(oracle_mod, K, dtype):
     rng = np.random.default_rng(1000 + K)
@@ -70,7 +70,7 @@ def test_worker_counts_and_ragged_tail(oracle_mod, K, dtype):
     check(oracle_mod, w, "K=%d" % K)
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 @pytest.mark.parametrize("P", [1, 2, 3, 4, 5, 7, 8, 9, 255, 1023, 1024, 1025, 4097, 262_145])
 def test_tiny_and_boundary_lengths(oracle_mod, P, dtype):
     w = W.make(3, P, dtype, [32, 57, 132], 1e-3, 1e-2, seed=P, device=DEV)
@@ -85,7 +85,7 @@ def test_all_64_workers_large(oracle_mod):
 
 
 # ------------------------------------------------------------------ segments
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
 def test_segments_at_odd_offsets(oracle_mod, dtype):
     P = 1_200_007
     off = [0, 1, 2, 3, 7, 8, 130, 131, 4099, 4100, 65_537, 262_143, 262_145, 700_001, P - 1, P]
@@ -153,6 +153,27 @@ def test_non_finite_inputs_propagate():
     assert np.isinf(agg[12_345]) and np.isnan(agg[40_000])
     assert np.isfinite(np.delete(agg, [12_345, 40_000])).all()
     assert np.isfinite(st[0, HEAD]) and np.isinf(st[0, HEAD + 1]) and np.isnan(st[0, HEAD + 2])
+
+
+def test_fp16_subnormals_and_loss_scale_overflow(oracle_mod):
+    """fp16 gradients are held to the fp32 tolerances (widening is exact, subnormals included).
+    Unscaled they sit in the subnormal range; scaled by 2^16 one worker overflows to Inf, which
+    shows in that worker's squared norm alone."""
+    K, P = 6, 700_003
+    w = W.make(K, P, torch.float32, [16, 32, 64, 64, 128, 256], 1e-6, 2e-5, seed=21, device=DEV)
+    small = [g.to(torch.float16) for g in w.grads]
+    sub = sum(int(((g != 0) & (g.abs() < 6.2e-5)).sum()) for g in small)
+    assert sub > K * P // 2                                   # mostly subnormal values
+    w.grads, w.dtype = small, torch.float16
+    check(oracle_mod, w, "fp16 subnormal")
+
+    w.grads = [(g.float() * 65536.0).to(torch.float16) for g in small]
+    check(oracle_mod, w, "fp16 loss-scaled")
+    w.grads[3][123_456] = float("inf")                        # what an overflowing scale leaves
+    _, st = run_gpu(w, stats_only=True)
+    n = st[0, HEAD:HEAD + K]
+    assert np.isinf(n[3]) and np.isfinite(np.delete(n, 3)).all()
+    assert not np.isfinite(st[0, 0]) and not np.isfinite(st[0, HEAD + K:]).any()
 
 
 # ------------------------------------------------------------------ behaviour of the entry point
