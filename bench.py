@@ -151,6 +151,7 @@ def main():
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
+    enqueued = time.perf_counter() - t0   # host side of the calls: marshalling, plan lookup, launches
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
@@ -204,6 +205,7 @@ def main():
         "elements_per_s": w.K * w.P / (elapsed / args.steps),
         "total_traffic_GBps": round(algo_bytes / (elapsed / args.steps) / 1e9, 2),
         "noise_scale": ns,
+        "host_enqueue_us_per_step": round(enqueued / args.steps * 1e6, 2),
         "roofline": {"bound": "hbm", "kernel": "stream_pass_kernel",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
