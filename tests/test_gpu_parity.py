@@ -100,6 +100,32 @@ def test_segments_at_odd_offsets(oracle_mod, dtype):
     assert np.array_equal(st, st2)
 
 
+RANDOM_K = [1, 2, 3, 5, 8, 9, 16, 17, 31, 32, 33, 40, 48, 49, 57, 64]   # every unroll / load width
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("K", RANDOM_K)
+def test_random_segmentations_for_every_kernel_shape(oracle_mod, K, dtype):
+    """Random lengths and random segment cuts (neighbouring cuts, cuts inside one vector, cuts at
+    tile edges) for every combination of unroll factor, load width and storage type."""
+    rng = np.random.default_rng(5000 + K * 3 + [torch.float32, torch.bfloat16, torch.float16].index(dtype))
+    for rep in range(2):
+        P = int(rng.integers(1, 40)) if (rep == 1 and K % 3 == 0) else int(rng.integers(5_000, 400_000))
+        S = int(min(P, rng.integers(1, 25)))
+        cuts = set(int(c) for c in rng.choice(np.arange(1, P), size=S - 1, replace=False)) if S > 1 else set()
+        for c in list(cuts)[:3]:                    # one-element segments and a cut at a tile edge
+            if c + 1 < P:
+                cuts.add(c + 1)
+        tile_elems = 512 * 4
+        if P > tile_elems + 1:
+            cuts.add(tile_elems)
+        off = [0] + sorted(cuts) + [P]
+        sig = np.exp(rng.uniform(np.log(1e-3), np.log(1e-1), size=len(off) - 1))
+        b = rng.integers(1, 1025, size=K)
+        w = W.make(K, P, dtype, b, 1e-3, sig, seed=900 + K + rep, device=DEV, segment_offsets=off)
+        check(oracle_mod, w, "random K=%d P=%d S=%d" % (K, P, len(off) - 1))
+
+
 def test_many_one_element_segments(oracle_mod):
     P = 3000
     w = W.make(4, P, torch.float32, [32, 64, 96, 128], 1e-3, 1e-2, seed=5, device=DEV,
