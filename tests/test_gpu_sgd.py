@@ -40,7 +40,8 @@ def check_step(oracle_mod, w, lr, wd, where):
 
 @pytest.mark.parametrize("K,dtype", [(1, torch.float32), (4, torch.float32), (8, torch.bfloat16),
                                      (16, torch.bfloat16), (32, torch.float32), (33, torch.float32),
-                                     (49, torch.float32), (64, torch.bfloat16)])
+                                     (49, torch.float32), (64, torch.bfloat16),
+                                     (2, torch.float16), (48, torch.float16)])
 def test_fused_sgd_step(oracle_mod, K, dtype):
     rng = np.random.default_rng(300 + K)
     P = int(rng.integers(150_000, 250_000)) * 4 + int(rng.integers(1, 4))
