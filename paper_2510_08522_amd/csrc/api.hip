@@ -107,43 +107,47 @@ void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int
     const int VEC = vec_elems(K, dtype);
     const int64_t tile = (int64_t)kBlock * unroll_for(K);  // vectors per block iteration
     const int64_t nvec = ceil_div(P, VEC);
-    const int64_t ntiles = ceil_div(nvec, tile);
+    // Spans start at multiples of a wave's worth of vectors (1 KB of every stream), so that the
+    // 64 lanes of a wave stay on whole cache lines; a block's last tile may be partial.
+    const int64_t gran = 64;
+    const int64_t ngran = ceil_div(nvec, gran);
     if (max_grid < 1) max_grid = 1;
 
     {
-        // Every block owns one contiguous span of whole tiles.  A span costs its tiles plus a
-        // fixed amount per piece (pipeline start, boundary vectors, final flush, block reduction:
-        // about what 128 KB of streaming takes), and the spans are cut so that the costs are
-        // equal; without segments the tile counts of two blocks differ by at most one.
-        L.grid = (int)std::min<int64_t>(max_grid, ntiles);
-        const double tile_bytes = (double)tile * VEC * (dtype == kF32 ? 4 : 2) * K;
-        const double piece_cost = kPieceCostBytes / tile_bytes;            // in tiles
+        // Every block owns one contiguous span.  A span costs its length plus a fixed amount per
+        // piece (pipeline start, boundary vectors, final flush, block reduction: about what
+        // 128 KB of streaming takes), and the spans are cut so that the costs are equal; without
+        // segments the lengths of two spans differ by at most one granule.  A block is started
+        // for every kBlock vectors at least, up to max_grid.
+        L.grid = (int)std::min<int64_t>(std::min(max_grid, ngran), std::max<int64_t>(1, nvec / kBlock));
+        const double gran_bytes = (double)gran * VEC * (dtype == kF32 ? 4 : 2) * K;
+        const double piece_cost = kPieceCostBytes / gran_bytes;           // in granules
         std::vector<int64_t> cuts;                                         // vectors where a new piece starts
         for (int j = 1; j < S; ++j) cuts.push_back(offsets[j] / VEC);
-        const double total_cost = (double)ntiles + piece_cost * (double)cuts.size();
+        const double total_cost = (double)ngran + piece_cost * (double)cuts.size();
         std::vector<int64_t> span_begin(L.grid + 1, 0);                    // first vector of every span
         {
             size_t c = 0;        // cuts already behind the walk
-            int64_t t = 0;       // tiles already dealt
+            int64_t t = 0;       // granules already dealt
             for (int b = 1; b < L.grid; ++b) {
                 const double want = total_cost * b / L.grid;
-                // advance tile by tile over the cuts, in one jump between them
-                while (t < ntiles) {
+                // advance granule by granule over the cuts, in one jump between them
+                while (t < ngran) {
                     const double here = (double)t + piece_cost * (double)c;
                     if (here >= want) break;
-                    const int64_t next_cut_tile = c < cuts.size() ? cuts[c] / tile : ntiles;
-                    if (next_cut_tile > t) {
+                    const int64_t next_cut = c < cuts.size() ? cuts[c] / gran : ngran;
+                    if (next_cut > t) {
                         const int64_t need = (int64_t)std::ceil(want - here);
-                        t = std::min<int64_t>(std::min(next_cut_tile, t + std::max<int64_t>(need, 1)), ntiles);
+                        t = std::min<int64_t>(std::min(next_cut, t + std::max<int64_t>(need, 1)), ngran);
                     } else {
-                        ++c;     // the cut lies in the tile the walk stands on
+                        ++c;     // the cut lies in the granule the walk stands on
                     }
                 }
-                // every block keeps at least one tile and leaves one for each block after it
-                t = std::max<int64_t>(t, span_begin[b - 1] / tile + 1);
-                t = std::min<int64_t>(t, ntiles - (L.grid - b));
-                span_begin[b] = t * tile;
-                while (c < cuts.size() && cuts[c] / tile < t) ++c;
+                // every block keeps at least one granule and leaves one for each block after it
+                t = std::max<int64_t>(t, span_begin[b - 1] / gran + 1);
+                t = std::min<int64_t>(t, ngran - (L.grid - b));
+                span_begin[b] = t * gran;
+                while (c < cuts.size() && cuts[c] / gran < t) ++c;
             }
             span_begin[L.grid] = nvec;
         }
