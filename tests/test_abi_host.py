@@ -4,6 +4,8 @@ every element exactly once."""
 import ctypes
 import os
 import re
+import shutil
+import subprocess
 
 import numpy as np
 import pytest
@@ -31,6 +33,29 @@ def test_library_exports_every_declared_symbol():
     # the Python layer carries the same names
     for n in names:
         assert hasattr(D, n), n
+
+
+@pytest.mark.skipif(shutil.which("gcc") is None, reason="no C compiler")
+def test_header_is_plain_c_and_links_from_a_c_program(tmp_path):
+    """The boundary is a C ABI: a strict C99 translation unit that includes the header, takes the
+    address of every declared function and calls the two that need no device."""
+    names = declared_functions()
+    src = tmp_path / "use_dynamix.c"
+    src.write_text(
+        '#include "dynamix.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        "    const void* fns[] = {%s};\n"
+        '    printf("%%d %%lld %%s\\n", (int)(sizeof fns / sizeof fns[0]),\n'
+        "           (long long)dynamix_stats_count(32, 148), dynamix_status_string(DYNAMIX_ERR_ALIGN));\n"
+        "    return fns[0] == 0;\n}\n" % ", ".join("(const void*)%s" % n for n in names))
+    exe = tmp_path / "use_dynamix"
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-Wno-pedantic",
+                    "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-ldynamix", "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 2)
+    assert int(out[0]) == len(names) and int(out[1]) == 149 * 72
+    assert out[2].strip() == "misaligned pointer"
 
 
 def test_stats_count_and_status_strings():
