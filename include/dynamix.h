@@ -2,8 +2,8 @@
  * dynamix.h -- C ABI of the per-step gradient aggregate + statistics path on one MI355X.
  *
  * Setting (paper: Background, "Distributed machine learning systems"; Problem Formulation,
- * "Action space and batch size adjustment"; Algorithm 1, the steps "compute gradient g_i and
- * update global model" and "collect performance metrics"): K bulk-synchronous data-parallel
+ * "Action space and batch size adjustment"; Algorithm 1, the gradient-and-model-update step and the
+ * metric-collection step of a training iteration): K bulk-synchronous data-parallel
  * workers hold a full model replica each, worker k computes its gradient g_k on a batch of its
  * own size b_k (an integer the agent moves inside [32, 1024]), and at the barrier the gradients
  * are combined.  The agent's state carries gradient statistics (Problem Formulation, "Training
@@ -109,8 +109,8 @@ int dynamix_grad_aggregate_stats_ex(const void* const* grads, const int32_t* bat
                                     float* out_agg, double* out_stats, void* stream);
 
 /*
- * The same pass with the model update fused in (Algorithm 1: "compute gradient g_i and update
- * global model"): instead of writing G, the kernel applies plain stochastic gradient descent with
+ * The same pass with the model update fused in (Algorithm 1, the model-update half of its
+ * gradient step): instead of writing G, the kernel applies plain stochastic gradient descent with
  * L2 weight decay in place,
  *     params[i] <- params[i] - lr * (G_i + weight_decay * params[i]),
  * which saves the write of G and the optimizer's later read of it.  params: DEVICE, P floats,

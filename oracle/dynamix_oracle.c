@@ -4,8 +4,8 @@
  * Plain CPU oracle for the per-step gradient synchronisation of K bulk-synchronous
  * data-parallel workers that run with different per-worker batch sizes (paper: Background,
  * "Distributed machine learning systems"; Problem Formulation, "Action space and batch size
- * adjustment"; Algorithm 1, the step "compute gradient g_i and update global model" and the
- * following "collect performance metrics" step), together with the gradient statistics that
+ * adjustment"; Algorithm 1, the gradient-and-model-update step and the metric-collection step
+ * that follows it), together with the gradient statistics that
  * the agent's state and reward use (Problem Formulation, "Training Statistical Efficiency
  * Metrics": sigma_norm and sigma_norm^2; reward term -eta(sigma_norm^2 + sigma_norm)) and the
  * gradient noise scale the evaluation leans on (Evaluation, discussion of the batch size
@@ -201,8 +201,8 @@ int dynamix_oracle_aggregate_stats(const void *const *grads, const int32_t *b, i
 }
 
 /*
- * The model update that follows the aggregation (Algorithm 1: "compute gradient g_i and update
- * global model"; the paper trains with SGD and Adam and prints no update formula).  Plain
+ * The model update that follows the aggregation (Algorithm 1, the model-update half of its
+ * gradient step; the paper trains with SGD and Adam and prints no update formula).  Plain
  * stochastic gradient descent with L2 weight decay, the textbook rule:
  *     p_i <- p_i - lr * (G_i + wd * p_i)
  * with G from the aggregation above, evaluated in long double and rounded once to double.
