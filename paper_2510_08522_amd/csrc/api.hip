@@ -118,8 +118,8 @@ void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int
         // piece (pipeline start, boundary vectors, final flush, block reduction: about what
         // 128 KB of streaming takes), and the spans are cut so that the costs are equal; without
         // segments the lengths of two spans differ by at most one granule.  A block is started
-        // for every kBlock vectors at least, up to max_grid.
-        L.grid = (int)std::min<int64_t>(std::min(max_grid, ngran), std::max<int64_t>(1, nvec / kBlock));
+        // for every 512 vectors at least, up to max_grid.
+        L.grid = (int)std::min<int64_t>(std::min(max_grid, ngran), std::max<int64_t>(1, nvec / 512));
         const double gran_bytes = (double)gran * VEC * (dtype == kF32 ? 4 : 2) * K;
         const double piece_cost = kPieceCostBytes / gran_bytes;           // in granules
         std::vector<int64_t> cuts;                                         // vectors where a new piece starts

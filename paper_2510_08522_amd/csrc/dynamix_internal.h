@@ -6,7 +6,10 @@
 namespace dynamix {
 
 constexpr int kKMax = 64;        // workers per call; pointers and weights travel by value
-constexpr int kBlock = 512;      // threads per block of the streaming pass: 8 wave64, one block per CU
+// Threads per block of the streaming pass: four wave64, one per SIMD of the compute unit the
+// block has to itself, so that a wave may use up to 512 registers (four waves read as fast as
+// eight: measured).
+constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / 64;
 constexpr int kHead = 8;         // scalars in front of the per-worker entries of a record
 

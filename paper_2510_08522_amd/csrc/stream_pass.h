@@ -8,6 +8,8 @@
 // bound by HBM bandwidth (about one flop per byte), so there is no LDS tiling of the data and no
 // MFMA: the work is coalesced 128-bit loads, fp32 FMAs and one block reduction per piece.
 #pragma once
+#include <type_traits>
+
 #include "dynamix_internal.h"
 
 namespace dynamix {
@@ -128,10 +130,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const void* base, in
 
 constexpr int kMasked = 0x7ffffff0;  // a lane offset beyond every tile: the access is dropped
 
-// The eight waves of a block leave every barrier in lockstep, and two waves that share a SIMD
-// then want the vector ALU and the memory pipeline at the same moments (measured: 4 % of the
-// bandwidth against two independent blocks of four waves).  Wave w therefore idles w * 1024
-// clocks (at most 3 microseconds) when a piece starts and after each flush.
+// The waves of a block leave every barrier in lockstep and then want the memory pipeline at the
+// same moments.  Wave w therefore idles w * 1024 clocks (a microsecond or so) when a piece starts
+// and after each flush.
 __device__ __forceinline__ void stagger_waves(int tid)
 {
     for (int i = 0; i < (tid >> 6); ++i) __builtin_amdgcn_s_sleep(16);
@@ -143,9 +144,28 @@ __device__ __forceinline__ void stagger_waves(int tid)
 // policy, issuing wave or size).  So G of kStageTiles tiles is parked in LDS and the whole block
 // (the only one on its compute unit) writes it out between two barriers, when none of its loads
 // is outstanding.
-// 152 KB is what the 160 KB of LDS leave beside the wave partials in whole 8 KB tiles; more
-// capacity means fewer, larger flushes, which are cheaper per byte (measured).
+// More capacity means fewer, larger flushes, which are cheaper per byte (measured).  The LDS part
+// is 152 KB, what the 160 KB leave beside the wave partials.  When it is full for the first time
+// in a flush cycle every lane moves its own slots into a bank of registers (152 of the 512 a
+// wave may use here; plain copies with constant indices, no synchronisation, since a lane reads
+// only what it wrote) and the LDS fills once more; then both are written out.
 constexpr int kStageBytes = 152 * 1024;
+
+// The bank lives in the accumulation half of the register file, which nothing else in this
+// kernel uses; the moves are written out so that the register allocator never has to weigh these
+// values against the vector registers of the hot loop.
+__device__ __forceinline__ uint32_t to_acc(uint32_t v)
+{
+    uint32_t a;
+    asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(a) : "v"(v));
+    return a;
+}
+__device__ __forceinline__ uint32_t from_acc(uint32_t a)
+{
+    uint32_t v;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
 template <int K, int DT, int U>
 struct Shape {
     static constexpr int kLW = load_words_for(K);                  // words per lane and load
@@ -159,7 +179,8 @@ struct Shape {
 };
 
 template <int K, int DT, int U>
-__global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) void stream_pass_kernel(
+    const StreamArgs a)
 {
     typedef Shape<K, DT, U> Sh;
     typedef Words<Sh::kLW> Wd;
@@ -370,8 +391,16 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
             }
             int staged = 0;            // tiles parked in LDS
             int64_t v_staged = v0;     // first of them
+            uint32_t bank[NB * U * Q * LW];   // the register bank (accumulation registers): NB more
+                                              // tiles, parked before those in the LDS
+            int64_t v_bank = v0;       // first tile of the bank
             bool more = true;
-            while (more) {
+            // One tile.  With the bank the loop over tiles exists twice (two instantiations of this
+            // body): once for the first half of a flush cycle, while the bank is empty, and once
+            // for the second half, during which the bank is only kept, never redefined, so that
+            // it costs the loop no register copies.
+            auto tile_body = [&](auto mode) {
+                constexpr int kMode = decltype(mode)::value;   // 0 first half, 1 second half, 2 no bank
                 // Software pipeline without extra registers: as pass 2 finishes with a worker's
                 // vector, the same registers take that worker's vector of the next tile, so
                 // loads are issued all through the arithmetic.  After the last tile the
@@ -404,8 +433,28 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                 if (want_agg) {
                     if (staged == 0) v_staged = v0;
                     ++staged;
-                    if (staged == NB || !more) {
+                    if (kMode == 0 ? !more : (staged == NB || !more)) {
                         __syncthreads();
+                        if constexpr (kMode == 1) {
+#pragma unroll
+                            for (int j = 0; j < NB; ++j) {
+                                const int64_t vj = v_bank + j * TILE;
+                                const __amdgpu_buffer_rsrc_t r =
+                                    tile_rsrc(out, vj * (VEC * 4), tile_vectors(vj) * (VEC * 4));
+#pragma unroll
+                                for (int u = 0; u < U; ++u)
+#pragma unroll
+                                    for (int h = 0; h < Q; ++h)
+                                    {
+                                        wvec t;
+#pragma unroll
+                                        for (int c = 0; c < LW; ++c)
+                                            t[c] = from_acc(bank[((j * U + u) * Q + h) * LW + c]);
+                                        Wd::template store<kStorePolicy>(
+                                            t, r, (u * kBlock + tid) * (VEC * 4) + VB * h);
+                                    }
+                            }
+                        }
                         for (int j = 0; j < staged; ++j) {
                             const int64_t vj = v_staged + j * TILE;
                             const __amdgpu_buffer_rsrc_t r =
@@ -450,6 +499,32 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(const StreamArgs a)
                                 rp, (u * kBlock + tid) * (VEC * 4) + VB * h);
                 }
                 v0 = vn;
+            };
+            // The bank is used where a lane parks 16 bytes at a time (K <= 32, where the written
+            // share of the traffic is largest).  With narrower vectors the loop itself needs all
+            // 256 vector registers, the compiler would start to move values into accumulation
+            // registers on its own, and some instantiations built that way gave wrong sums.
+            constexpr bool kBank = LW == 4;
+            while (!kBank && more) tile_body(std::integral_constant<int, 2>{});
+            while (kBank && more) {
+                // first half of the cycle: until the LDS is full (or the run ends, which flushes)
+                do {
+                    tile_body(std::integral_constant<int, 0>{});
+                } while (more && staged < NB);
+                if (!more) break;
+                // every lane moves its own slots into the bank, and the LDS fills once more
+#pragma unroll
+                for (int j = 0; j < NB * U * Q; ++j) {
+                    const wvec t = stage[j][tid];
+#pragma unroll
+                    for (int c = 0; c < LW; ++c) bank[j * LW + c] = to_acc(t[c]);
+                }
+                v_bank = v_staged;
+                staged = 0;
+                // second half: until the flush of bank and LDS (which resets staged)
+                do {
+                    tile_body(std::integral_constant<int, 1>{});
+                } while (staged != 0);
             }
         }
 

@@ -118,7 +118,7 @@ def check_cover(K, P, dtype, off, max_blocks):
     """Replay the kernel's iteration space on the host: the body of whole vectors of every piece
     plus its boundary vectors must touch each element exactly once."""
     vec = (1 if K > 48 else 2 if K > 32 else 4) * (1 if dtype == 0 else 2)   # elements per lane and load
-    tile = 512 * unroll_for(K)                              # vectors per block iteration
+    tile = 256 * unroll_for(K)                              # vectors per block iteration
     pcs = D.dynamix_plan_describe(K, P, dtype, off, max_blocks)
     assert len(pcs) >= 1
     assert (np.diff(pcs[:, 5]) >= 0).all()                      # pieces sorted by owning block
@@ -164,7 +164,7 @@ def test_plan_covers_every_element_once(dtype):
 
 def test_plan_for_the_headline_shape_is_balanced():
     pcs = check_cover(32, 138_000_000, 0, None, 256)
-    tiles = -(-(pcs[:, 1] - pcs[:, 0]) // 512)
+    tiles = -(-(pcs[:, 1] - pcs[:, 0]) // 256)
     assert len(pcs) == 256                                       # one piece per compute unit
     assert tiles.max() - tiles.min() <= 1
 
