@@ -5,6 +5,7 @@ instantiations are split over 24 translation units that compile in parallel.
 Run as `python -m paper_2510_08522_amd.build`.
 """
 import os
+import re
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
@@ -33,14 +34,55 @@ def _jobs():
     return jobs
 
 
+_KERNEL = re.compile(r"stream_pass_kernelILi(\d+)ELi(\d+)ELi(\d+)E")
+
+
+def _bank_registers(K, dtype, U):
+    """Accumulation registers the streaming pass uses on purpose (its register bank): the same
+    arithmetic as Shape<> in csrc/stream_pass.h."""
+    if K > 32:
+        return 0
+    LW, kBlock, stage = 4, 256, 152 * 1024
+    Q = (1 if dtype == 0 else 2)
+    slots = stage // (kBlock * LW * 4)
+    return (slots // (U * Q)) * U * Q * LW
+
+
+def _check_resources(remarks, src):
+    """The streaming pass must not spill and must not have values moved into accumulation
+    registers by the compiler (instantiations built that way have returned wrong sums on gfx950);
+    the only accumulation registers allowed are those of its explicit bank."""
+    name, bad = None, []
+    for line in remarks.splitlines():
+        if "Function Name:" in line:
+            m = _KERNEL.search(line)
+            name = tuple(int(x) for x in m.groups()) if m else None
+        elif name is not None:
+            m = re.search(r"remark:\s+(AGPRs|ScratchSize \[bytes/lane\]): (\d+)", line)
+            if m and m.group(1) == "AGPRs" and int(m.group(2)) != _bank_registers(*name):
+                bad.append("K=%d dtype=%d: %s accumulation registers, expected %d"
+                           % (name[0], name[1], m.group(2), _bank_registers(*name)))
+            if m and m.group(1).startswith("Scratch") and int(m.group(2)) != 0:
+                bad.append("K=%d dtype=%d: %s bytes of scratch" % (name[0], name[1], m.group(2)))
+    if bad:
+        raise RuntimeError("register allocation of %s is not as required:\n  %s"
+                           % (os.path.basename(src), "\n  ".join(bad)))
+
+
 def _compile(job):
     src, obj, defs = job
     cmd = [HIPCC] + FLAGS + defs + ["-c", src, "-o", obj]
+    check = src.endswith("stream_pass_inst.hip")
+    if check:
+        cmd.append("-Rpass-analysis=kernel-resource-usage")
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
+    lines = [l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l]
     if r.returncode != 0:
-        raise RuntimeError("hipcc failed: %s\n%s" % (" ".join(cmd), out))
-    return out
+        raise RuntimeError("hipcc failed: %s\n%s" % (" ".join(cmd), "\n".join(lines)))
+    if check:
+        _check_resources(r.stdout, src)
+        lines = [l for l in lines if "remark:" not in l and "Rpass-analysis" not in l]
+    return "\n".join(lines)
 
 
 def build(verbose=False, workers=None):
