@@ -38,14 +38,17 @@ _KERNEL = re.compile(r"stream_pass_kernelILi(\d+)ELi(\d+)ELi(\d+)E")
 
 
 def _bank_registers(K, dtype, U):
-    """Accumulation registers the streaming pass uses on purpose (its register bank): the same
-    arithmetic as Shape<> in csrc/stream_pass.h."""
+    """Accumulation registers the streaming pass uses on purpose (its two register banks): the
+    same arithmetic as Shape<> in csrc/stream_pass.h."""
     if K > 32:
         return 0
     LW, kBlock, stage = 4, 256, 152 * 1024
     Q = (1 if dtype == 0 else 2)
     slots = stage // (kBlock * LW * 4)
-    return (slots // (U * Q)) * U * Q * LW
+    per_tile = U * Q * LW
+    first = (slots // (U * Q)) * per_tile
+    second = (256 - first) // per_tile * per_tile
+    return first + second
 
 
 def _check_resources(remarks, src):

@@ -174,7 +174,9 @@ struct Shape {
     static constexpr int kSize = DT == kF32 ? 4 : 2;               // bytes per element
     static constexpr int kQ = kVec / kLW;                          // LW-word pieces of G per vector
     static constexpr int kSlots = kStageBytes / (kBlock * kVB);    // LW-word slots per thread
-    static constexpr int kTiles = kSlots / (U * kQ);               // tiles per flush
+    static constexpr int kTiles = kSlots / (U * kQ);               // tiles the LDS holds
+    // a second, smaller bank in what the first leaves of the 256 accumulation registers
+    static constexpr int kTiles2 = (256 - kTiles * U * kQ * kLW) / (U * kQ * kLW);
     static_assert(kTiles >= 1, "a tile of G must fit the staging area");
 };
 
@@ -186,6 +188,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     typedef Words<Sh::kLW> Wd;
     typedef typename Wd::type wvec;
     constexpr int LW = Sh::kLW, VB = Sh::kVB, VEC = Sh::kVec, Q = Sh::kQ, NB = Sh::kTiles;
+    constexpr int NB2 = Sh::kTiles2;
     constexpr int W = 2 * K + 1;
     constexpr int64_t TILE = (int64_t)kBlock * U;   // vectors per block iteration
     __shared__ wvec stage[NB * U * Q][kBlock];
@@ -391,16 +394,19 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             }
             int staged = 0;            // tiles parked in LDS
             int64_t v_staged = v0;     // first of them
-            uint32_t bank[NB * U * Q * LW];   // the register bank (accumulation registers): NB more
-                                              // tiles, parked before those in the LDS
-            int64_t v_bank = v0;       // first tile of the bank
+            // the register banks (accumulation registers): NB and NB2 more tiles, parked before
+            // those in the LDS
+            uint32_t bank[NB * U * Q * LW];
+            uint32_t bank2[(NB2 > 0 ? NB2 : 1) * U * Q * LW];
+            int64_t v_bank = v0, v_bank2 = v0;   // first tile of each bank
             bool more = true;
             // One tile.  With the bank the loop over tiles exists twice (two instantiations of this
             // body): once for the first half of a flush cycle, while the bank is empty, and once
             // for the second half, during which the bank is only kept, never redefined, so that
             // it costs the loop no register copies.
             auto tile_body = [&](auto mode) {
-                constexpr int kMode = decltype(mode)::value;   // 0 first half, 1 second half, 2 no bank
+                // 0: both banks empty; 1: first bank full; 2: both full; 3: kernel without banks
+                constexpr int kMode = decltype(mode)::value;
                 // Software pipeline without extra registers: as pass 2 finishes with a worker's
                 // vector, the same registers take that worker's vector of the next tile, so
                 // loads are issued all through the arithmetic.  After the last tile the
@@ -433,9 +439,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 if (want_agg) {
                     if (staged == 0) v_staged = v0;
                     ++staged;
-                    if (kMode == 0 ? !more : (staged == NB || !more)) {
+                    if (kMode <= 1 ? !more : (staged == NB || !more)) {
                         __syncthreads();
-                        if constexpr (kMode == 1) {
+                        if constexpr (kMode == 1 || kMode == 2) {
 #pragma unroll
                             for (int j = 0; j < NB; ++j) {
                                 const int64_t vj = v_bank + j * TILE;
@@ -450,6 +456,26 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #pragma unroll
                                         for (int c = 0; c < LW; ++c)
                                             t[c] = from_acc(bank[((j * U + u) * Q + h) * LW + c]);
+                                        Wd::template store<kStorePolicy>(
+                                            t, r, (u * kBlock + tid) * (VEC * 4) + VB * h);
+                                    }
+                            }
+                        }
+                        if constexpr (kMode == 2) {
+#pragma unroll
+                            for (int j = 0; j < NB2; ++j) {
+                                const int64_t vj = v_bank2 + j * TILE;
+                                const __amdgpu_buffer_rsrc_t r =
+                                    tile_rsrc(out, vj * (VEC * 4), tile_vectors(vj) * (VEC * 4));
+#pragma unroll
+                                for (int u = 0; u < U; ++u)
+#pragma unroll
+                                    for (int h = 0; h < Q; ++h)
+                                    {
+                                        wvec t;
+#pragma unroll
+                                        for (int c = 0; c < LW; ++c)
+                                            t[c] = from_acc(bank2[((j * U + u) * Q + h) * LW + c]);
                                         Wd::template store<kStorePolicy>(
                                             t, r, (u * kBlock + tid) * (VEC * 4) + VB * h);
                                     }
@@ -505,14 +531,14 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             // 256 vector registers, the compiler would start to move values into accumulation
             // registers on its own, and some instantiations built that way gave wrong sums.
             constexpr bool kBank = LW == 4;
-            while (!kBank && more) tile_body(std::integral_constant<int, 2>{});
+            while (!kBank && more) tile_body(std::integral_constant<int, 3>{});
             while (kBank && more) {
-                // first half of the cycle: until the LDS is full (or the run ends, which flushes)
+                // until the LDS is full (or the run ends, which flushes)
                 do {
                     tile_body(std::integral_constant<int, 0>{});
                 } while (more && staged < NB);
                 if (!more) break;
-                // every lane moves its own slots into the bank, and the LDS fills once more
+                // every lane moves its own slots into the first bank, and the LDS fills again
 #pragma unroll
                 for (int j = 0; j < NB * U * Q; ++j) {
                     const wvec t = stage[j][tid];
@@ -521,9 +547,24 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 }
                 v_bank = v_staged;
                 staged = 0;
-                // second half: until the flush of bank and LDS (which resets staged)
+                if constexpr (NB2 > 0) {
+                    do {
+                        tile_body(std::integral_constant<int, 1>{});
+                    } while (more && staged < NB2);
+                    if (!more) break;
+                    // the second, smaller bank
+#pragma unroll
+                    for (int j = 0; j < NB2 * U * Q; ++j) {
+                        const wvec t = stage[j][tid];
+#pragma unroll
+                        for (int c = 0; c < LW; ++c) bank2[j * LW + c] = to_acc(t[c]);
+                    }
+                    v_bank2 = v_staged;
+                    staged = 0;
+                }
+                // until the flush of banks and LDS (which resets staged)
                 do {
-                    tile_body(std::integral_constant<int, 1>{});
+                    tile_body(std::integral_constant<int, 2>{});
                 } while (staged != 0);
             }
         }
