@@ -126,6 +126,29 @@ def test_random_segmentations_for_every_kernel_shape(oracle_mod, K, dtype):
         check(oracle_mod, w, "random K=%d P=%d S=%d" % (K, P, len(off) - 1))
 
 
+@pytest.mark.parametrize("K,dtype,U,NB,NB2", [(32, torch.float32, 1, 38, 26), (8, torch.float32, 4, 9, 7),
+                                              (16, torch.bfloat16, 2, 9, 7), (2, torch.float16, 8, 2, 2)])
+def test_tile_counts_around_the_staging_phases(oracle_mod, monkeypatch, K, dtype, U, NB, NB2):
+    """One block walks the whole vector, so that the number of tiles it parks is known: just below,
+    at and just above each hand-over (LDS full -> first register bank -> second bank -> flush),
+    with a ragged last tile."""
+    monkeypatch.setenv("DYNAMIX_MAX_BLOCKS", "1")
+    vec = 4 * (1 if dtype == torch.float32 else 2)
+    tile = 256 * U * vec                                   # elements per block iteration
+    cycle = 2 * NB + NB2
+    rng = np.random.default_rng(77 + K)
+    for t in [1, NB - 1, NB, NB + 1, NB + NB2 - 1, NB + NB2, NB + NB2 + 1, cycle - 1, cycle,
+              cycle + 1, cycle + NB, 2 * cycle + NB + NB2 + 1]:
+        if t < 1:
+            continue
+        P = t * tile - int(rng.integers(0, vec + 2))       # sometimes whole, sometimes ragged
+        b = rng.integers(8, 1025, size=K)
+        w = W.make(K, P, dtype, b, 1e-3, 1e-2, seed=500 + t, device=DEV)
+        assert len(D.dynamix_plan_describe(K, P, {torch.float32: 0, torch.bfloat16: 1,
+                                                  torch.float16: 2}[dtype], None, 1)) == 1
+        check(oracle_mod, w, "phases K=%d tiles=%d" % (K, t))
+
+
 def test_many_one_element_segments(oracle_mod):
     P = 3000
     w = W.make(4, P, torch.float32, [32, 64, 96, 128], 1e-3, 1e-2, seed=5, device=DEV,
