@@ -193,6 +193,12 @@ int     dynamix_timing_begin(int32_t capacity);
 int32_t dynamix_timing_count(void);
 int     dynamix_timing_read(int32_t index, float* stream_pass_ms, float* final_reduce_ms);
 
+/*
+ * Environment: DYNAMIX_MAX_BLOCKS=n (n >= 1) caps the number of blocks the streaming pass is
+ * launched with; it is read whenever a plan is built (first call for a shape).  A tuning and
+ * testing aid: results do not depend on it beyond the order of the fp64 partial sums.
+ */
+
 /* Frees every cached plan and workspace.  The caller must have synchronised all streams that
  * were used with the library.  Returns a dynamix_status. */
 int dynamix_release_cached(void);
