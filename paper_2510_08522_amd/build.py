@@ -40,9 +40,9 @@ _KERNEL = re.compile(r"stream_pass_kernelILi(\d+)ELi(\d+)ELi(\d+)E")
 def _bank_registers(K, dtype, U):
     """Accumulation registers the streaming pass uses on purpose (its two register banks): the
     same arithmetic as Shape<> in csrc/stream_pass.h."""
-    if K > 32:
+    if K > 44:
         return 0
-    LW, kBlock, stage = 4, 256, 152 * 1024
+    LW, kBlock, stage = (4 if K <= 32 else 2), 256, 152 * 1024
     Q = (1 if dtype == 0 else 2)
     slots = stage // (kBlock * LW * 4)
     per_tile = U * Q * LW

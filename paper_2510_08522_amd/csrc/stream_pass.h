@@ -526,11 +526,10 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 }
                 v0 = vn;
             };
-            // The bank is used where a lane parks 16 bytes at a time (K <= 32, where the written
-            // share of the traffic is largest).  With narrower vectors the loop itself needs all
-            // 256 vector registers, the compiler would start to move values into accumulation
-            // registers on its own, and some instantiations built that way gave wrong sums.
-            constexpr bool kBank = LW == 4;
+            // The banks are used up to K = 44.  Above, the loop itself needs all 256 vector
+            // registers, the compiler would start to move values into accumulation registers on
+            // its own, and some instantiations built that way gave wrong sums.
+            constexpr bool kBank = K <= 44;
             while (!kBank && more) tile_body(std::integral_constant<int, 3>{});
             while (kBank && more) {
                 // until the LDS is full (or the run ends, which flushes)

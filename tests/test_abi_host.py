@@ -226,11 +226,11 @@ def test_fused_sgd_entry_validates_on_the_host():
 
 def test_build_check_of_register_allocation():
     """The build refuses a streaming-pass instantiation that spills or that has values placed in
-    accumulation registers other than its two banks (256 of them for K <= 32, none above)."""
+    accumulation registers other than its two banks (256 of them for K <= 44, none above)."""
     from paper_2510_08522_amd import build as Bd
     assert [Bd._bank_registers(K, d, U) for K, d, U in
-            [(1, 0, 8), (8, 0, 4), (16, 1, 2), (32, 0, 1), (32, 2, 1), (33, 0, 1), (64, 1, 1)]] == \
-        [256, 256, 256, 256, 256, 0, 0]
+            [(1, 0, 8), (8, 0, 4), (16, 1, 2), (32, 0, 1), (32, 2, 1), (33, 0, 1), (44, 1, 1), (45, 0, 1),
+             (64, 1, 1)]] == [256, 256, 256, 256, 256, 256, 256, 0, 0]
     tag = "[-Rpass-analysis=kernel-resource-usage]"
     fn = "x.hip:1:1: remark: Function Name: _ZN7dynamix18stream_pass_kernelILi%dELi0ELi1EEEvNS_10StreamArgsE " + tag
 
@@ -239,7 +239,7 @@ def test_build_check_of_register_allocation():
                           "x.hip:1:1: remark:     AGPRs: %d %s" % (agprs, tag),
                           "x.hip:1:1: remark:     ScratchSize [bytes/lane]: %d %s" % (scratch, tag)])
     Bd._check_resources(remarks(32, 256, 0), "x.hip")
-    Bd._check_resources(remarks(40, 0, 0), "x.hip")
-    for bad in (remarks(32, 152, 0), remarks(32, 256, 8), remarks(40, 6, 0)):
+    Bd._check_resources(remarks(50, 0, 0), "x.hip")
+    for bad in (remarks(32, 152, 0), remarks(32, 256, 8), remarks(50, 6, 0)):
         with pytest.raises(RuntimeError):
             Bd._check_resources(bad, "x.hip")

@@ -127,13 +127,14 @@ def test_random_segmentations_for_every_kernel_shape(oracle_mod, K, dtype):
 
 
 @pytest.mark.parametrize("K,dtype,U,NB,NB2", [(32, torch.float32, 1, 38, 26), (8, torch.float32, 4, 9, 7),
-                                              (16, torch.bfloat16, 2, 9, 7), (2, torch.float16, 8, 2, 2)])
+                                              (16, torch.bfloat16, 2, 9, 7), (2, torch.float16, 8, 2, 2),
+                                              (40, torch.float32, 1, 76, 52), (44, torch.bfloat16, 1, 38, 26)])
 def test_tile_counts_around_the_staging_phases(oracle_mod, monkeypatch, K, dtype, U, NB, NB2):
     """One block walks the whole vector, so that the number of tiles it parks is known: just below,
     at and just above each hand-over (LDS full -> first register bank -> second bank -> flush),
     with a ragged last tile."""
     monkeypatch.setenv("DYNAMIX_MAX_BLOCKS", "1")
-    vec = 4 * (1 if dtype == torch.float32 else 2)
+    vec = (4 if K <= 32 else 2) * (1 if dtype == torch.float32 else 2)   # elements per vector
     tile = 256 * U * vec                                   # elements per block iteration
     cycle = 2 * NB + NB2
     rng = np.random.default_rng(77 + K)
