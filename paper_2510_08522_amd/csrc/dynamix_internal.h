@@ -22,8 +22,8 @@ constexpr int kDtypes = 3;
 constexpr int unroll_for(int K) { return K <= 2 ? 8 : K <= 8 ? 4 : K <= 16 ? 2 : 1; }
 
 // 32-bit words a lane loads at a time: four (128-bit loads) up to 32 workers, two up to 48, one
-// above, so that the K vectors of a lane plus the 2K+1 running sums stay within 256 registers at
-// eight waves per compute unit.
+// above, so that the K vectors of a lane plus the 2K+1 running sums stay within the 256 vector
+// registers an instruction can address.
 constexpr int load_words_for(int K) { return K > 48 ? 1 : K > 32 ? 2 : 4; }
 // elements per vector
 constexpr int vec_elems(int K, int dtype) { return load_words_for(K) * (dtype == kF32 ? 1 : 2); }

@@ -141,19 +141,22 @@ __device__ __forceinline__ void stagger_waves(int tid)
 // Staging of the aggregate.  A store that enters a compute unit's memory pipeline while that unit
 // has loads in flight holds the pipeline up for hundreds of cycles (measured: one 16-byte store
 // per lane and tile costs a 32-stream read 27 % of its bandwidth, whatever the store's cache
-// policy, issuing wave or size).  So G of kStageTiles tiles is parked in LDS and the whole block
-// (the only one on its compute unit) writes it out between two barriers, when none of its loads
-// is outstanding.
-// More capacity means fewer, larger flushes, which are cheaper per byte (measured).  The LDS part
-// is 152 KB, what the 160 KB leave beside the wave partials.  When it is full for the first time
-// in a flush cycle every lane moves its own slots into a bank of registers (152 of the 512 a
-// wave may use here; plain copies with constant indices, no synchronisation, since a lane reads
-// only what it wrote) and the LDS fills once more; then both are written out.
+// policy, issuing wave or size), and a byte written to HBM costs the read stream of the whole
+// chip several bytes, the more the thinner the writes are spread in time (measured).  So
+// finished tiles of G are kept on chip as long as there is room, and the whole block (the only
+// one on its compute unit) writes them out in one burst between two barriers, when none of its
+// loads is outstanding.  Room is 152 KB of LDS (what the 160 KB leave beside the wave partials)
+// and, up to K = 44, the 256 accumulation registers of every lane: when the LDS is full for the
+// first time in a flush cycle every lane moves its own slots into a first bank of registers,
+// when it is full again (as far as the remaining registers reach) into a second, and after the
+// third filling everything is written out.  A lane reads back only what it wrote, so the moves
+// need no synchronisation.
 constexpr int kStageBytes = 152 * 1024;
 
-// The bank lives in the accumulation half of the register file, which nothing else in this
+// The banks live in the accumulation half of the register file, which nothing else in this
 // kernel uses; the moves are written out so that the register allocator never has to weigh these
-// values against the vector registers of the hot loop.
+// values against the vector registers of the hot loop (left to itself it produced
+// instantiations with corrupted sums on this target).
 __device__ __forceinline__ uint32_t to_acc(uint32_t v)
 {
     uint32_t a;
