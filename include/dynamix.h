@@ -74,6 +74,8 @@ enum {
  * grads            HOST array of K DEVICE pointers.  grads[k] holds P elements of `dtype`,
  *                  contiguous, 16-byte aligned, read-only for the call, owned by the caller.
  *                  The K buffers are independent allocations; none may overlap out_agg.
+ *                  (Speed only: K slices of one large allocation stream about 8 % faster on
+ *                  MI355X than K allocations made one by one.)
  * batch_sizes      HOST array of K per-worker batch sizes b_k, each > 0.
  * K, P             number of workers (1..DYNAMIX_K_MAX) and elements per gradient (>= 1).
  * dtype            a dynamix_dtype.
