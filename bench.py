@@ -90,6 +90,10 @@ def main():
                     help="time one input set over and over even when it fits the 256 MB "
                          "memory-side cache (default: rotate copies of it so every step reads "
                          "from HBM)")
+    ap.add_argument("--stagger-elems", type=int, default=0,
+                    help="with --separate-buffers: start buffer k that many elements times k into "
+                         "its allocation (a multiple of 8), so that the K streams do not sit at the "
+                         "same offsets of their allocations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 2^28 floats (1 GiB read, 1 GiB "
                          "written) three times, as the known-size reference for HBM byte counters")
@@ -110,7 +114,8 @@ def main():
     D.binding.load()                      # no fallback: raises if the library cannot be loaded
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    w = W.config(args.workload, device=dev, one_allocation=not args.separate_buffers)
+    w = W.config(args.workload, device=dev, one_allocation=not args.separate_buffers,
+                 stagger_elems=args.stagger_elems if args.separate_buffers else 0)
     out_agg = torch.empty(w.P, dtype=torch.float32, device=dev)
     out_stats = torch.empty((1 + w.S, D.DYNAMIX_STATS_HEAD + 2 * w.K), dtype=torch.float64,
                             device=dev)
@@ -208,7 +213,9 @@ def main():
         "config": {"workload": describe(w), "K": w.K, "P": w.P, "segments": w.S,
                    "input_dtype": "bf16" if w.itemsize == 2 else "fp32",
                    "bytes_read_per_step": read_bytes, "seed": w.seed,
-                   "buffers": "K allocations" if args.separate_buffers else "K rows of one allocation",
+                   "buffers": ("K allocations" + (", staggered by %d elements" % args.stagger_elems
+                                                 if args.stagger_elems else ""))
+                   if args.separate_buffers else "K rows of one allocation",
                    "cache": cache_note},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "elements_per_s": w.K * w.P / (elapsed / args.steps),

@@ -74,8 +74,12 @@ enum {
  * grads            HOST array of K DEVICE pointers.  grads[k] holds P elements of `dtype`,
  *                  contiguous, 16-byte aligned, read-only for the call, owned by the caller.
  *                  The K buffers are independent allocations; none may overlap out_agg.
- *                  (Speed only: K slices of one large allocation stream about 8 % faster on
- *                  MI355X than K allocations made one by one.)
+ *                  (Speed only: on MI355X the K streams should not sit at the same offsets of
+ *                  equally aligned allocations, where the same elements of all workers fall into
+ *                  the same memory channels: K allocations made one by one stream 8 % slower than
+ *                  K slices of one allocation, and as fast again when buffer k starts k * 4352
+ *                  bytes into its allocation; 4 KB to 8 KB per buffer help, 16 KB to 256 KB do
+ *                  not.)
  * batch_sizes      HOST array of K per-worker batch sizes b_k, each > 0.
  * K, P             number of workers (1..DYNAMIX_K_MAX) and elements per gradient (>= 1).
  * dtype            a dynamix_dtype.

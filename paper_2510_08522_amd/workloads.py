@@ -77,7 +77,7 @@ def _segment_sizes(rng, P, S, lo, hi):
 
 
 def make(K, P, dtype, batch_sizes, m, sigma, seed, device="cpu", segment_offsets=None,
-         name="custom", one_allocation=True):
+         name="custom", one_allocation=True, stagger_elems=0):
     """Draw one workload.  sigma is a scalar, or one value per segment.
 
     The K buffers are independent as far as the aggregation entry point is concerned (it takes
@@ -114,7 +114,12 @@ def make(K, P, dtype, batch_sizes, m, sigma, seed, device="cpu", segment_offsets
         else:
             eps.mul_(sig_el).mul_(float(1.0 / np.sqrt(float(b[k]))))
         eps.add_(mu)
-        if store is None:
+        if store is None and stagger_elems:
+            # buffer k starts k * stagger_elems elements into an allocation of its own
+            own = torch.empty(P + K * stagger_elems, dtype=dtype, device=dev)
+            own[k * stagger_elems:k * stagger_elems + P].copy_(eps)
+            grads.append(own[k * stagger_elems:k * stagger_elems + P])
+        elif store is None:
             grads.append(eps.to(dtype).contiguous())
         else:
             store[k, :P].copy_(eps)           # same rounding as .to(dtype)
@@ -142,7 +147,7 @@ SHAPES = {
 }
 
 
-def config(name, device="cpu", P=None, one_allocation=True):
+def config(name, device="cpu", P=None, one_allocation=True, stagger_elems=0):
     """One of the named configurations C1..C5.  P overrides the length (the batch sizes, the
     generator parameters and the segment structure stay those of the configuration), so that
     CPU tests can use the same recipe at a size the oracle finishes quickly."""
@@ -168,5 +173,6 @@ def config(name, device="cpu", P=None, one_allocation=True):
         off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
         sigma = np.exp(rng.uniform(np.log(1e-4), np.log(1e-1), size=S))
     w = make(K, P, dtype, np.asarray(b, dtype=np.int32), m, sigma, seed, device=device,
-             segment_offsets=off, name=name, one_allocation=one_allocation)
+             segment_offsets=off, name=name, one_allocation=one_allocation,
+             stagger_elems=stagger_elems)
     return w
