@@ -94,6 +94,8 @@ int env_int(const char* name, int fallback)
 
 // The work decomposition (pure host arithmetic, no HIP): pieces in block order, the first piece
 // of every block, and per record its piece range and element count.
+constexpr int64_t kMaxPieceVectors = (int64_t)1 << 25;   // a multiple of every tile size
+
 struct Layout {
     int grid = 0;
     std::vector<Piece> pieces;
@@ -160,15 +162,21 @@ void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int
             int b = (int)(std::upper_bound(span_begin.begin(), span_begin.end(), v_lo) -
                           span_begin.begin()) - 1;
             for (; b < L.grid && span_begin[b] < v_hi; ++b) {
-                Piece pc;
-                pc.v_begin = std::max(v_lo, span_begin[b]);
-                pc.v_end = std::min(v_hi, span_begin[b + 1]);
-                pc.v_step = tile;
-                pc.e_lo = std::max(lo, pc.v_begin * VEC);
-                pc.e_hi = std::min(hi, pc.v_end * VEC);
-                pc.block = b;
-                L.pieces.push_back(pc);
-                per_block[b] += 1;
+                // a piece is kept below 2^25 vectors: the kernel addresses the aggregate of a
+                // piece with 32-bit byte offsets (at most 32 bytes of it per vector)
+                const int64_t p_begin = std::max(v_lo, span_begin[b]);
+                const int64_t p_end = std::min(v_hi, span_begin[b + 1]);
+                for (int64_t v = p_begin; v < p_end; v += kMaxPieceVectors) {
+                    Piece pc;
+                    pc.v_begin = v;
+                    pc.v_end = std::min(p_end, v + kMaxPieceVectors);
+                    pc.v_step = tile;
+                    pc.e_lo = std::max(lo, pc.v_begin * VEC);
+                    pc.e_hi = std::min(hi, pc.v_end * VEC);
+                    pc.block = b;
+                    L.pieces.push_back(pc);
+                    per_block[b] += 1;
+                }
             }
         }
         int32_t acc = 0;

@@ -275,6 +275,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
         // speed: the vector is read twice (once per pass), eight workers at a time.
         auto boundary_vector = [&](int64_t v, int64_t lo, int64_t hi) {
             constexpr int CH = 8;   // workers whose loads are in flight together
+            // The two flags are derived again here, from pointers the compiler cannot trace back:
+            // otherwise it keeps them in a register across the hot loop, which has none to spare.
+            float* out_b = out;
+            const float* params_b = a.params;
+            asm volatile("" : "+s"(out_b), "+s"(params_b));
+            const bool want_b = out_b != nullptr, fused_b = params_b != nullptr;
             int off[VEC];
 #pragma unroll
             for (int c = 0; c < VEC; ++c) {
@@ -326,15 +332,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             }
 #pragma unroll
             for (int c = 0; c < VEC; ++c) A = __builtin_fmaf(Ge[c], Ge[c], A);
-            if (want_agg) {
-                const __amdgpu_buffer_rsrc_t r = tile_rsrc(out, v * (VEC * 4), VEC * 4);
+            if (want_b) {
+                const __amdgpu_buffer_rsrc_t r = tile_rsrc(out_b, v * (VEC * 4), VEC * 4);
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) {
                     const int oc = off[c] == kMasked ? kMasked : c * 4;
-                    float pc_old = 0.f;
-                    if (fused) pc_old = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, oc, 0, 0));
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(updated(Ge[c], pc_old)), r,
-                                                          oc, 0, 0);
+                    float res = Ge[c];
+                    if (fused_b) {
+                        const float pc_old =
+                            __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, oc, 0, 0));
+                        res = __builtin_fmaf(neg_lr, __builtin_fmaf(wd, pc_old, Ge[c]), pc_old);
+                    }
+                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(res), r, oc, 0, 0);
                 }
             }
 #pragma unroll
@@ -368,40 +377,73 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             // ---- the body: the hot loop.  A tile is kBlock * U vectors; the last one may be
             // shorter, in which case its descriptors are shorter and the lanes beyond read zero
             // and write nothing.
-            int64_t v0 = body_begin;
-            auto tile_vectors = [&](int64_t v) {
-                return v < body_end ? (int)min((int64_t)TILE, body_end - v) : 0;
+            //
+            // Which vectors make up a tile.  The K buffers of a caller often sit at the same
+            // offsets of equally aligned allocations; the same elements of all workers then fall
+            // into the same memory channels, and with tiles of 4 KB consecutive bytes per worker
+            // the K loads of a lane queue up behind each other (8 % of the bandwidth, measured).
+            // So, with 16-byte vectors, the body is taken in groups of 16 tiles, and tile i of a
+            // group takes from each of the group's 16 U units of 4 KB one chunk of 256 bytes
+            // (chunk (i + unit) mod 16): every load instruction of a wave then touches four
+            // units instead of a quarter of one.  What is left after the last whole group is
+            // taken in consecutive tiles.
+            constexpr bool kSpread = LW == 4;
+            constexpr int GS = kSpread ? 4 : 0;          // log2 of the tiles per group
+            constexpr int64_t GROUP = TILE << GS;
+            const int64_t body_vectors = body_end - body_begin;
+            // (tile counts fit 32 bits: a tile is at least 1024 elements)
+            const int body_tiles = (int)((body_vectors + TILE - 1) / TILE);
+            const int full_groups = kSpread ? (int)(body_vectors / GROUP) : 0;
+            struct Where {
+                int64_t v;    // first vector of the tile's group: where its descriptors start
+                int count;    // vectors they cover, to the end of the group or of the body
             };
-            const bool long_run = body_end - v0 > 8 * TILE;   // staggering pays only then
+            auto where = [&](int t) -> Where {
+                if (t >= body_tiles) return {body_end, 0};
+                const int64_t v = body_begin + (int64_t)(t >> GS) * GROUP;
+                return {v, (int)min(GROUP, body_end - v)};
+            };
+            // the vector, counted from where(t).v, that this lane handles as its u-th of tile t
+            auto lane_vec_of = [&](int lane, int t, int u) -> int {
+                const int i = t & ((1 << GS) - 1);
+                if (kSpread && (t >> GS) < full_groups) {
+                    const int unit = lane >> 4;
+                    return ((u * 16 + unit) * 16 + ((i + unit) & 15)) * 16 + (lane & 15);
+                }
+                return (i * U + u) * kBlock + lane;
+            };
+            auto lane_vec = [&](int t, int u) -> int { return lane_vec_of(tid, t, u); };
+            int t = 0;   // tile of the body being processed
+            const bool long_run = body_vectors > 8 * TILE;   // staggering pays only then
             if (long_run) stagger_waves(tid);
             // The K vectors of every lane.  A tile is always loaded one iteration ahead: by
             // pass 2 of the tile before it, or here for the first one.
             wvec x[U][K];
             wvec xp[U][Q];   // the parameters of the tile (fused update only; else never read)
             {
-                const int bytes = tile_vectors(v0) * VB;
+                const Where w0 = where(0);
 #pragma unroll
                 for (int u = 0; u < U; ++u)
 #pragma unroll
                     for (int k = 0; k < K; ++k)
                         x[u][k] = Wd::template load<kLoadPolicy>(
-                            tile_rsrc(a.g[k], v0 * VB, bytes), (u * kBlock + tid) * VB);
+                            tile_rsrc(a.g[k], w0.v * VB, w0.count * VB), lane_vec(0, u) * VB);
                 const __amdgpu_buffer_rsrc_t rp =
-                    tile_rsrc(a.params, v0 * (VEC * 4), fused ? tile_vectors(v0) * (VEC * 4) : 0);
+                    tile_rsrc(a.params, w0.v * (VEC * 4), fused ? w0.count * (VEC * 4) : 0);
 #pragma unroll
                 for (int u = 0; u < U; ++u)
 #pragma unroll
                     for (int h = 0; h < Q; ++h)
                         xp[u][h] = Wd::template load<kLoadPolicy>(
-                            rp, (u * kBlock + tid) * (VEC * 4) + VB * h);
+                            rp, lane_vec(0, u) * (VEC * 4) + VB * h);
             }
             int staged = 0;            // tiles parked in LDS
-            int64_t v_staged = v0;     // first of them
+            int t_staged = 0;          // first of them
             // the register banks (accumulation registers): NB and NB2 more tiles, parked before
             // those in the LDS
             uint32_t bank[NB * U * Q * LW];
             uint32_t bank2[(NB2 > 0 ? NB2 : 1) * U * Q * LW];
-            int64_t v_bank = v0, v_bank2 = v0;   // first tile of each bank
+            int t_bank = 0, t_bank2 = 0;   // first tile of each bank
             bool more = true;
             // One tile.  With the bank the loop over tiles exists twice (two instantiations of this
             // body): once for the first half of a flush cycle, while the bank is empty, and once
@@ -414,9 +456,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 // vector, the same registers take that worker's vector of the next tile, so
                 // loads are issued all through the arithmetic.  After the last tile the
                 // descriptor gets zero length and the loads touch no memory.
-                const int64_t vn = v0 + TILE;
-                const int next_bytes = tile_vectors(vn) * VB;
-                more = next_bytes > 0;
+                const int tn = t + 1;
+                const Where wn = where(tn);
+                more = wn.count > 0;
 
                 float G[U][VEC];
 #pragma unroll
@@ -440,16 +482,26 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 // yet issued any for the next one, so once all waves are here the block has no
                 // load in flight.  The parked tiles are written out and the stores waited for.
                 if (want_agg) {
-                    if (staged == 0) v_staged = v0;
+                    if (staged == 0) t_staged = t;
                     ++staged;
                     if (kMode <= 1 ? !more : (staged == NB || !more)) {
                         __syncthreads();
+                        // the store addresses are worked out here, from a copy of the lane number
+                        // the compiler cannot see through: otherwise it prepares them ahead of
+                        // the loop and keeps them in registers the loop needs
+                        int lane_f = tid;
+                        asm volatile("" : "+v"(lane_f));
+                        // one descriptor over the whole body for the stores (a piece has at most
+                        // 2^26 vectors, so byte offsets inside it fit the 32-bit lane offset)
+                        const __amdgpu_buffer_rsrc_t r = tile_rsrc(
+                            out, body_begin * (VEC * 4), (int)(body_vectors * (VEC * 4)));
+                        auto out_off = [&](int tj, int u) -> int {
+                            return ((tj >> GS) * (int)GROUP + lane_vec_of(lane_f, tj, u)) * (VEC * 4);
+                        };
                         if constexpr (kMode == 1 || kMode == 2) {
 #pragma unroll
                             for (int j = 0; j < NB; ++j) {
-                                const int64_t vj = v_bank + j * TILE;
-                                const __amdgpu_buffer_rsrc_t r =
-                                    tile_rsrc(out, vj * (VEC * 4), tile_vectors(vj) * (VEC * 4));
+                                const int tj = t_bank + j;
 #pragma unroll
                                 for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -460,16 +512,14 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                                         for (int c = 0; c < LW; ++c)
                                             t[c] = from_acc(bank[((j * U + u) * Q + h) * LW + c]);
                                         Wd::template store<kStorePolicy>(
-                                            t, r, (u * kBlock + tid) * (VEC * 4) + VB * h);
+                                            t, r, out_off(tj, u) + VB * h);
                                     }
                             }
                         }
                         if constexpr (kMode == 2) {
 #pragma unroll
                             for (int j = 0; j < NB2; ++j) {
-                                const int64_t vj = v_bank2 + j * TILE;
-                                const __amdgpu_buffer_rsrc_t r =
-                                    tile_rsrc(out, vj * (VEC * 4), tile_vectors(vj) * (VEC * 4));
+                                const int tj = t_bank2 + j;
 #pragma unroll
                                 for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -480,21 +530,19 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                                         for (int c = 0; c < LW; ++c)
                                             t[c] = from_acc(bank2[((j * U + u) * Q + h) * LW + c]);
                                         Wd::template store<kStorePolicy>(
-                                            t, r, (u * kBlock + tid) * (VEC * 4) + VB * h);
+                                            t, r, out_off(tj, u) + VB * h);
                                     }
                             }
                         }
                         for (int j = 0; j < staged; ++j) {
-                            const int64_t vj = v_staged + j * TILE;
-                            const __amdgpu_buffer_rsrc_t r =
-                                tile_rsrc(out, vj * (VEC * 4), tile_vectors(vj) * (VEC * 4));
+                            const int tj = t_staged + j;
 #pragma unroll
                             for (int u = 0; u < U; ++u)
 #pragma unroll
                                 for (int h = 0; h < Q; ++h)
                                     Wd::template store<kStorePolicy>(
                                         stage[(j * U + u) * Q + h][tid], r,
-                                        (u * kBlock + tid) * (VEC * 4) + VB * h);
+                                        out_off(tj, u) + VB * h);
                         }
                         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                         __syncthreads();
@@ -503,31 +551,33 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                     }
                 }
 
+                const int next_bytes = wn.count * VB;
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
+                    const int next_vec = lane_vec(tn, u);
 #pragma unroll
                     for (int k = 0; k < K; ++k) {
                         pass2(x[u][k], G[u], k);
                         // order the load after the last use of the registers it overwrites (the
                         // empty asm ties its address to this worker's updated sums), or the
                         // scheduler hoists all K loads and the live ranges double
-                        int pf_off = (u * kBlock + tid) * VB;
+                        int pf_off = next_vec * VB;
                         asm volatile("" : "+v"(pf_off) : "v"(n[k]), "v"(d[k]));
                         x[u][k] = Wd::template load<kLoadPolicy>(
-                            tile_rsrc(a.g[k], vn * VB, next_bytes), pf_off);
+                            tile_rsrc(a.g[k], wn.v * VB, next_bytes), pf_off);
                     }
                 }
                 {
                     const __amdgpu_buffer_rsrc_t rp = tile_rsrc(
-                        a.params, vn * (VEC * 4), fused ? tile_vectors(vn) * (VEC * 4) : 0);
+                        a.params, wn.v * (VEC * 4), fused ? wn.count * (VEC * 4) : 0);
 #pragma unroll
                     for (int u = 0; u < U; ++u)
 #pragma unroll
                         for (int h = 0; h < Q; ++h)
                             xp[u][h] = Wd::template load<kLoadPolicy>(
-                                rp, (u * kBlock + tid) * (VEC * 4) + VB * h);
+                                rp, lane_vec(tn, u) * (VEC * 4) + VB * h);
                 }
-                v0 = vn;
+                t = tn;
             };
             // The banks are used up to K = 44.  Above, the loop itself needs all 256 vector
             // registers, the compiler would start to move values into accumulation registers on
@@ -547,7 +597,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #pragma unroll
                     for (int c = 0; c < LW; ++c) bank[j * LW + c] = to_acc(t[c]);
                 }
-                v_bank = v_staged;
+                t_bank = t_staged;
                 staged = 0;
                 if constexpr (NB2 > 0) {
                     do {
@@ -561,7 +611,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #pragma unroll
                         for (int c = 0; c < LW; ++c) bank2[j * LW + c] = to_acc(t[c]);
                     }
-                    v_bank2 = v_staged;
+                    t_bank2 = t_staged;
                     staged = 0;
                 }
                 // until the flush of banks and LDS (which resets staged)
@@ -587,11 +637,15 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             }
         }
         __syncthreads();
-        if (tid < W) {
+        // (the lane number is hidden from the compiler here so that the address of the store is
+        // worked out now and not kept in registers from the start of the kernel)
+        int tid_e = tid;
+        asm volatile("" : "+v"(tid_e));
+        if (tid_e < W) {
             double s = 0.0;
 #pragma unroll
-            for (int wv = 0; wv < kWaves; ++wv) s += static_cast<double>(wave_part[wv][tid]);
-            a.partials[static_cast<int64_t>(p) * W + tid] = s;
+            for (int wv = 0; wv < kWaves; ++wv) s += static_cast<double>(wave_part[wv][tid_e]);
+            a.partials[static_cast<int64_t>(p) * W + tid_e] = s;
         }
         __syncthreads();
     }

@@ -180,6 +180,14 @@ def test_spans_start_on_wave_boundaries_and_small_inputs_use_every_unit():
     assert len(check_cover(4, 4_096, 0, None, 256)) == 2
 
 
+def test_long_spans_are_cut_into_pieces_the_kernel_can_address():
+    # the kernel addresses the aggregate of a piece with 32-bit byte offsets: 2^25 vectors at most
+    pcs = check_cover(64, (1 << 26) + 5, 0, None, 1)
+    assert len(pcs) == 3 and (pcs[:, 1] - pcs[:, 0]).max() == 1 << 25
+    pcs = check_cover(64, (1 << 26) + 5, 0, [0, 7, (1 << 25) + 9, (1 << 26) + 5], 2)
+    assert (pcs[:, 1] - pcs[:, 0]).max() <= 1 << 25
+
+
 def test_plan_describe_rejects_bad_shapes():
     with pytest.raises(D.DynamixError):
         D.dynamix_plan_describe(0, 10, 0)
