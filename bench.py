@@ -79,9 +79,9 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=16_000_000,
                     help="elements per worker the CPU oracle is timed on (0: skip)")
     ap.add_argument("--cpu-threads", type=int, default=16)
-    ap.add_argument("--separate-buffers", action="store_true",
-                    help="allocate the K gradient buffers one by one instead of as K rows of one "
-                         "allocation")
+    ap.add_argument("--one-allocation", action="store_true",
+                    help="make the K gradient buffers rows of one allocation instead of K "
+                         "allocations made one by one")
     ap.add_argument("--settle-seconds", type=float, default=2.0,
                     help="run the step untimed for this long before the warm-up steps: right after "
                          "other heavy GPU work the device takes a second or two to reach its steady "
@@ -91,9 +91,9 @@ def main():
                          "memory-side cache (default: rotate copies of it so every step reads "
                          "from HBM)")
     ap.add_argument("--stagger-elems", type=int, default=0,
-                    help="with --separate-buffers: start buffer k that many elements times k into "
-                         "its allocation (a multiple of 8), so that the K streams do not sit at the "
-                         "same offsets of their allocations")
+                    help="without --one-allocation: start buffer k that many elements times k "
+                         "into its allocation (a multiple of 8), so that the K streams do not sit "
+                         "at the same offsets of their allocations")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain elementwise copy of 2^28 floats (1 GiB read, 1 GiB "
                          "written) three times, as the known-size reference for HBM byte counters")
@@ -114,8 +114,8 @@ def main():
     D.binding.load()                      # no fallback: raises if the library cannot be loaded
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    w = W.config(args.workload, device=dev, one_allocation=not args.separate_buffers,
-                 stagger_elems=args.stagger_elems if args.separate_buffers else 0)
+    w = W.config(args.workload, device=dev, one_allocation=args.one_allocation,
+                 stagger_elems=0 if args.one_allocation else args.stagger_elems)
     out_agg = torch.empty(w.P, dtype=torch.float32, device=dev)
     out_stats = torch.empty((1 + w.S, D.DYNAMIX_STATS_HEAD + 2 * w.K), dtype=torch.float64,
                             device=dev)
@@ -215,7 +215,7 @@ def main():
                    "bytes_read_per_step": read_bytes, "seed": w.seed,
                    "buffers": ("K allocations" + (", staggered by %d elements" % args.stagger_elems
                                                  if args.stagger_elems else ""))
-                   if args.separate_buffers else "K rows of one allocation",
+                   if not args.one_allocation else "K rows of one allocation",
                    "cache": cache_note},
         "pct_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "elements_per_s": w.K * w.P / (elapsed / args.steps),

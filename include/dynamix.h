@@ -74,11 +74,11 @@ enum {
  * grads            HOST array of K DEVICE pointers.  grads[k] holds P elements of `dtype`,
  *                  contiguous, 16-byte aligned, read-only for the call, owned by the caller.
  *                  The K buffers are independent allocations; none may overlap out_agg.
- *                  (Speed only: on MI355X the K streams should not sit at the same offsets of
- *                  equally aligned allocations, where the same elements of all workers fall into
- *                  the same memory channels: K allocations made one by one stream 8 % slower than
- *                  K slices of one allocation, and as fast again when buffer k starts k * 4352
- *                  bytes into its allocation; 4 KB to 8 KB per buffer help, 16 KB to 256 KB do
+ *                  (Speed only: with 8 to 32 workers the kernel reads interleaved 256-byte
+ *                  chunks, which keeps equally placed buffers, e.g. allocations a multiple of
+ *                  16 MB apart, from meeting in the same memory channels; it does so when every
+ *                  gradient buffer and the output start on 256-byte boundaries, and falls back to
+ *                  consecutive 4 KB tiles, up to 8 % slower for such placements, when one does
  *                  not.)
  * batch_sizes      HOST array of K per-worker batch sizes b_k, each > 0.
  * K, P             number of workers (1..DYNAMIX_K_MAX) and elements per gradient (>= 1).
@@ -100,7 +100,8 @@ enum {
  * propagate by IEEE rules.  The library keeps a small workspace per (device, stream, shape),
  * allocated on the first call with that shape and reused afterwards; two calls that share it
  * must be ordered on that stream.  For fixed inputs, shape and device the results are bitwise
- * reproducible (fixed-order reductions, no atomics).
+ * reproducible (fixed-order reductions, no atomics); the order of the sums, not the aggregate,
+ * depends on whether all buffers start on 256-byte boundaries.
  */
 int dynamix_grad_aggregate_stats(const void* const* grads, const int32_t* batch_sizes,
                                  int32_t K, int64_t P, int32_t dtype,
@@ -203,6 +204,8 @@ int     dynamix_timing_read(int32_t index, float* stream_pass_ms, float* final_r
  * Environment: DYNAMIX_MAX_BLOCKS=n (n >= 1) caps the number of blocks the streaming pass is
  * launched with; it is read whenever a plan is built (first call for a shape).  A tuning and
  * testing aid: results do not depend on it beyond the order of the fp64 partial sums.
+ * DYNAMIX_SPREAD=0 keeps the streaming pass on consecutive tiles also where it would interleave
+ * chunks (see `grads` above); read at every call; same kind of aid.
  */
 
 /* Frees every cached plan and workspace.  The caller must have synchronised all streams that

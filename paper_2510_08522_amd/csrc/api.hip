@@ -110,8 +110,10 @@ void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int
     const int64_t tile = (int64_t)kBlock * unroll_for(K);  // vectors per block iteration
     const int64_t nvec = ceil_div(P, VEC);
     // Spans start at multiples of a wave's worth of vectors (1 KB of every stream), so that the
-    // 64 lanes of a wave stay on whole cache lines; a block's last tile may be partial.
-    const int64_t gran = 64;
+    // 64 lanes of a wave stay on whole cache lines; a block's last tile may be partial.  Kernels
+    // that interleave chunks of 4 KB units start their groups at multiples of 256 vectors, so
+    // their spans start there (otherwise every block would begin with a short tile).
+    const int64_t gran = interleaves(K) ? 256 : 64;
     const int64_t ngran = ceil_div(nvec, gran);
     if (max_grid < 1) max_grid = 1;
 
@@ -348,6 +350,13 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     sa.params = params;
     sa.lr = lr;
     sa.wd = weight_decay;
+    {
+        // The interleaved tile order reads and writes 256-byte chunks: it is used when every
+        // buffer starts on such a boundary (DYNAMIX_SPREAD=0 turns it off, a tuning aid).
+        uintptr_t low = reinterpret_cast<uintptr_t>(out_agg) | reinterpret_cast<uintptr_t>(params);
+        for (int k = 0; k < K; ++k) low |= reinterpret_cast<uintptr_t>(grads[k]);
+        sa.spread = (low & 255u) == 0 && env_int("DYNAMIX_SPREAD", 1) != 0;
+    }
     fa.B = (double)B;
     fa.partials = pl->d_partials;
     fa.rec_range = pl->d_rec_range;

@@ -25,6 +25,9 @@ constexpr int unroll_for(int K) { return K <= 2 ? 8 : K <= 8 ? 4 : K <= 16 ? 2 :
 // above, so that the K vectors of a lane plus the 2K+1 running sums stay within the 256 vector
 // registers an instruction can address.
 constexpr int load_words_for(int K) { return K > 48 ? 1 : K > 32 ? 2 : 4; }
+// Whether the streaming pass for K workers may take its tiles as interleaved 256-byte chunks
+// (see stream_pass.h); the host then starts every block's span at a multiple of 4 KB.
+constexpr bool interleaves(int K) { return load_words_for(K) == 4 && K >= 8; }
 // elements per vector
 constexpr int vec_elems(int K, int dtype) { return load_words_for(K) * (dtype == kF32 ? 1 : 2); }
 
@@ -49,6 +52,9 @@ struct StreamArgs {
     double* partials;            // [pieces][2K+1]: A, n_0..n_{K-1}, d_0..d_{K-1}
     float* params;               // fused model update: p <- p - lr (G + wd p) in place; else null
     float lr, wd;
+    // Non-zero: every worker buffer and the output start at a multiple of 256 bytes, and the
+    // kernel may take its tiles as 256-byte chunks of several 4 KB units (see stream_pass.h).
+    int32_t spread;
 };
 
 struct FinalArgs {

@@ -381,35 +381,49 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             // Which vectors make up a tile.  The K buffers of a caller often sit at the same
             // offsets of equally aligned allocations; the same elements of all workers then fall
             // into the same memory channels, and with tiles of 4 KB consecutive bytes per worker
-            // the K loads of a lane queue up behind each other (8 % of the bandwidth, measured).
+            // the K loads of a lane queue up behind each other (8 % of the bandwidth at K = 32
+            // with buffers a multiple of 16 MB apart, measured).
             // So, with 16-byte vectors, the body is taken in groups of 16 tiles, and tile i of a
             // group takes from each of the group's 16 U units of 4 KB one chunk of 256 bytes
             // (chunk (i + unit) mod 16): every load instruction of a wave then touches four
             // units instead of a quarter of one.  What is left after the last whole group is
-            // taken in consecutive tiles.
-            constexpr bool kSpread = LW == 4;
+            // taken in consecutive tiles.  The aggregate is written in the same chunks, which
+            // costs more than it gains where the write is a large part of the traffic: below
+            // eight workers the tiles stay consecutive (measured: 2 to 4 % slower otherwise).
+            constexpr bool kSpread = interleaves(K);
             constexpr int GS = kSpread ? 4 : 0;          // log2 of the tiles per group
             constexpr int64_t GROUP = TILE << GS;
+            // The chunks only pay when they are whole cache lines, so the groups start at a
+            // multiple of 256 vectors (the caller says whether the buffers themselves are aligned;
+            // a.spread is zero otherwise, and everything is taken in consecutive tiles); the
+            // vectors in front of that are taken as one short tile of their own.
             const int64_t body_vectors = body_end - body_begin;
+            const bool spread = kSpread && a.spread != 0;
+            const int pre = spread ? (int)min((int64_t)((-body_begin) & 255), body_vectors) : 0;
+            const int has_pre = pre > 0 ? 1 : 0;
+            const int64_t groups_begin = body_begin + pre;
             // (tile counts fit 32 bits: a tile is at least 1024 elements)
-            const int body_tiles = (int)((body_vectors + TILE - 1) / TILE);
-            const int full_groups = kSpread ? (int)(body_vectors / GROUP) : 0;
+            const int body_tiles = has_pre + (int)((body_end - groups_begin + TILE - 1) / TILE);
+            const int full_groups = spread ? (int)((body_end - groups_begin) / GROUP) : 0;
             struct Where {
                 int64_t v;    // first vector of the tile's group: where its descriptors start
                 int count;    // vectors they cover, to the end of the group or of the body
             };
             auto where = [&](int t) -> Where {
                 if (t >= body_tiles) return {body_end, 0};
-                const int64_t v = body_begin + (int64_t)(t >> GS) * GROUP;
+                if (t < has_pre) return {body_begin, pre};
+                const int64_t v = groups_begin + (int64_t)((t - has_pre) >> GS) * GROUP;
                 return {v, (int)min(GROUP, body_end - v)};
             };
             // the vector, counted from where(t).v, that this lane handles as its u-th of tile t
             auto lane_vec_of = [&](int lane, int t, int u) -> int {
-                const int i = t & ((1 << GS) - 1);
-                if (kSpread && (t >> GS) < full_groups) {
+                const int tq = t - has_pre;   // -1 for the short tile in front
+                if (kSpread && tq >= 0 && (tq >> GS) < full_groups) {
+                    const int i = tq & 15;
                     const int unit = lane >> 4;
                     return ((u * 16 + unit) * 16 + ((i + unit) & 15)) * 16 + (lane & 15);
                 }
+                const int i = tq < 0 ? 0 : tq & ((1 << GS) - 1);
                 return (i * U + u) * kBlock + lane;
             };
             auto lane_vec = [&](int t, int u) -> int { return lane_vec_of(tid, t, u); };
@@ -496,7 +510,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                         const __amdgpu_buffer_rsrc_t r = tile_rsrc(
                             out, body_begin * (VEC * 4), (int)(body_vectors * (VEC * 4)));
                         auto out_off = [&](int tj, int u) -> int {
-                            return ((tj >> GS) * (int)GROUP + lane_vec_of(lane_f, tj, u)) * (VEC * 4);
+                            const int tq = tj - has_pre;
+                            const int first = tq < 0 ? 0 : pre + (tq >> GS) * (int)GROUP;
+                            return (first + lane_vec_of(lane_f, tj, u)) * (VEC * 4);
                         };
                         if constexpr (kMode == 1 || kMode == 2) {
 #pragma unroll

@@ -82,8 +82,9 @@ def make(K, P, dtype, batch_sizes, m, sigma, seed, device="cpu", segment_offsets
 
     The K buffers are independent as far as the aggregation entry point is concerned (it takes
     K pointers).  With one_allocation they are rows of a single allocation made before anything
-    else (rows padded to a multiple of 16 bytes), otherwise K allocations made one by one; on
-    the device the former is about 5 % faster to stream (placement in physical memory)."""
+    else (rows padded to a multiple of 16 bytes, so most rows start off the 256-byte boundaries
+    the kernel's interleaved tile order needs), otherwise K allocations made one by one (which
+    torch places on 512-byte boundaries)."""
     dev = torch.device(device)
     store = None
     if one_allocation:

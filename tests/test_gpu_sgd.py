@@ -49,7 +49,8 @@ def test_fused_sgd_step(oracle_mod, K, dtype):
     check_step(oracle_mod, w, lr=0.1, wd=5e-4, where="sgd K=%d" % K)
 
 
-def test_fused_sgd_across_the_staging_phases(oracle_mod, monkeypatch):
+@pytest.mark.parametrize("one_allocation", [True, False])
+def test_fused_sgd_across_the_staging_phases(oracle_mod, monkeypatch, one_allocation):
     """One block, enough tiles to fill the LDS and both register banks more than once, so that
     updated parameters pass through every staging place before they are written."""
     monkeypatch.setenv("DYNAMIX_MAX_BLOCKS", "1")
@@ -57,7 +58,7 @@ def test_fused_sgd_across_the_staging_phases(oracle_mod, monkeypatch):
     for K, dtype, tiles, tile in [(32, torch.float32, 2 * 102 + 38 + 3, 1024),
                                   (8, torch.bfloat16, 2 * 25 + 9 + 2, 256 * 4 * 8)]:
         w = W.make(K, tiles * tile - 5, dtype, rng.integers(8, 1025, size=K), 1e-3, 1e-2,
-                   seed=600 + K, device=DEV)
+                   seed=600 + K, device=DEV, one_allocation=one_allocation)
         check_step(oracle_mod, w, lr=0.1, wd=5e-4, where="sgd phases K=%d" % K)
 
 
