@@ -54,16 +54,19 @@ struct Plan {
     int K = 0, dtype = 0;
     int64_t P = 0;
     std::vector<int64_t> offsets;  // empty without segments
-    int grid = 0, pieces = 0, records = 0;
+    int grid = 0, pieces = 0, n_tail = 0, records = 0, slices = 1;
     bool uploaded = false;
     std::vector<char> host;        // staging image of the tables
     size_t table_bytes = 0;
     char* blob = nullptr;          // device: tables followed by the partial sums
     const Piece* d_pieces = nullptr;
-    const int32_t* d_block_first = nullptr;
+    const int32_t* d_block_range = nullptr;
+    const int32_t* d_tail_order = nullptr;
     const int32_t* d_rec_range = nullptr;
     const double* d_rec_count = nullptr;
     double* d_partials = nullptr;
+    int32_t* d_queue = nullptr;    // tail pieces drawn so far in the running launch; zero between launches
+    double* d_slice_sums = nullptr;
     uint64_t last_use = 0;
     ~Plan()
     {
@@ -92,14 +95,22 @@ int env_int(const char* name, int fallback)
     return (v && *v) ? std::atoi(v) : fallback;
 }
 
-// The work decomposition (pure host arithmetic, no HIP): pieces in block order, the first piece
-// of every block, and per record its piece range and element count.
+// The work decomposition (pure host arithmetic, no HIP): pieces, the pieces of every block, the
+// order of the shared tail, and per record its piece range and element count.
 constexpr int64_t kMaxPieceVectors = (int64_t)1 << 25;   // a multiple of every tile size
+constexpr int kTailPermille = 30;           // share of the range that goes to the shared tail
+constexpr int kMaxSlices = 16;              // blocks of the final reduction that share record 0
+constexpr int kPiecesPerSlice = 96;         // ... one per that many pieces, from kMinSlicedPieces on
+constexpr int kMinSlicedPieces = 512;
+constexpr int kTailMinTiles = 2;            // tiles in its last (shortest) pieces
+constexpr int kTailMinTilesPerBlock = 64;   // shorter inputs get no tail
 
 struct Layout {
     int grid = 0;
-    std::vector<Piece> pieces;
-    std::vector<int32_t> block_first, rec_range;
+    std::vector<Piece> pieces;        // in ascending order of position
+    std::vector<int32_t> block_range; // [grid][2]: first and one-past-last piece of every block
+    std::vector<int32_t> tail_order;  // pieces of the shared tail in the order they are drawn
+    std::vector<int32_t> rec_range;
     std::vector<double> rec_count;
 };
 
@@ -114,60 +125,103 @@ void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int
     // that interleave chunks of 4 KB units start their groups at multiples of 256 vectors, so
     // their spans start there (otherwise every block would begin with a short tile).
     const int64_t gran = interleaves(K) ? 256 : 64;
-    const int64_t ngran = ceil_div(nvec, gran);
     if (max_grid < 1) max_grid = 1;
+    L.grid = (int)std::min<int64_t>(std::min(max_grid, ceil_div(nvec, gran)),
+                                    std::max<int64_t>(1, nvec / 512));
 
+    const int64_t ngran = ceil_div(nvec, gran);
+
+    // Every block owns one contiguous span.  A span costs its length plus a fixed amount per
+    // piece (pipeline start, boundary vectors, final flush, block reduction: about what
+    // 128 KB of streaming takes), and the spans are cut so that the costs are equal; without
+    // segments the lengths of two spans differ by at most one granule.  A block is started
+    // for every 512 vectors at least, up to max_grid.
+    std::vector<int64_t> span_begin(L.grid + 1, 0);                    // first vector of every span
     {
-        // Every block owns one contiguous span.  A span costs its length plus a fixed amount per
-        // piece (pipeline start, boundary vectors, final flush, block reduction: about what
-        // 128 KB of streaming takes), and the spans are cut so that the costs are equal; without
-        // segments the lengths of two spans differ by at most one granule.  A block is started
-        // for every 512 vectors at least, up to max_grid.
-        L.grid = (int)std::min<int64_t>(std::min(max_grid, ngran), std::max<int64_t>(1, nvec / 512));
         const double gran_bytes = (double)gran * VEC * (dtype == kF32 ? 4 : 2) * K;
         const double piece_cost = kPieceCostBytes / gran_bytes;           // in granules
         std::vector<int64_t> cuts;                                         // vectors where a new piece starts
         for (int j = 1; j < S; ++j) cuts.push_back(offsets[j] / VEC);
         const double total_cost = (double)ngran + piece_cost * (double)cuts.size();
-        std::vector<int64_t> span_begin(L.grid + 1, 0);                    // first vector of every span
-        {
-            size_t c = 0;        // cuts already behind the walk
-            int64_t t = 0;       // granules already dealt
-            for (int b = 1; b < L.grid; ++b) {
-                const double want = total_cost * b / L.grid;
-                // advance granule by granule over the cuts, in one jump between them
-                while (t < ngran) {
-                    const double here = (double)t + piece_cost * (double)c;
-                    if (here >= want) break;
-                    const int64_t next_cut = c < cuts.size() ? cuts[c] / gran : ngran;
-                    if (next_cut > t) {
-                        const int64_t need = (int64_t)std::ceil(want - here);
-                        t = std::min<int64_t>(std::min(next_cut, t + std::max<int64_t>(need, 1)), ngran);
-                    } else {
-                        ++c;     // the cut lies in the granule the walk stands on
-                    }
+        size_t c = 0;        // cuts already behind the walk
+        int64_t t = 0;       // granules already dealt
+        for (int b = 1; b < L.grid; ++b) {
+            const double want = total_cost * b / L.grid;
+            // advance granule by granule over the cuts, in one jump between them
+            while (t < ngran) {
+                const double here = (double)t + piece_cost * (double)c;
+                if (here >= want) break;
+                const int64_t next_cut = c < cuts.size() ? cuts[c] / gran : ngran;
+                if (next_cut > t) {
+                    const int64_t need = (int64_t)std::ceil(want - here);
+                    t = std::min<int64_t>(std::min(next_cut, t + std::max<int64_t>(need, 1)), ngran);
+                } else {
+                    ++c;     // the cut lies in the granule the walk stands on
                 }
-                // every block keeps at least one granule and leaves one for each block after it
-                t = std::max<int64_t>(t, span_begin[b - 1] / gran + 1);
-                t = std::min<int64_t>(t, ngran - (L.grid - b));
-                span_begin[b] = t * gran;
-                while (c < cuts.size() && cuts[c] / gran < t) ++c;
             }
-            span_begin[L.grid] = nvec;
+            // every block keeps at least one granule and leaves one for each block after it
+            t = std::max<int64_t>(t, span_begin[b - 1] / gran + 1);
+            t = std::min<int64_t>(t, ngran - (L.grid - b));
+            span_begin[b] = t * gran;
+            while (c < cuts.size() && cuts[c] / gran < t) ++c;
         }
-        std::vector<int32_t> per_block(L.grid, 0);
+        span_begin[L.grid] = nvec;
+    }
+
+    // The shared tail.  Compute units do not stream equally fast (on MI355X the blocks of a
+    // 2.7 ms launch finish over a range of 160 us, the units of every other XCD about 1 % later
+    // than the rest), so with equal spans the launch ends with a few blocks running alone.  The
+    // block of a long span therefore only owns its front; the last few percent are cut into short
+    // pieces, each half of what is left and the last ones kTailMinTiles tiles, that any block
+    // draws from a counter once its own part is done: first the longest piece of every span, then
+    // the second of every span, and so on.  (They are taken from every span, not from the end of
+    // the whole range: blocks that all work within a few megabytes of each other stream a third
+    // slower per tile, measured.)  Environment, tuning aids read when a plan is built:
+    // DYNAMIX_TAIL_PERMILLE, the share of a span; DYNAMIX_TAIL_MIN, the shortest piece.
+    struct Sub {
+        int64_t begin;   // first vector
+        int owner;       // block, or -1 - round for a piece of the tail
+    };
+    std::vector<Sub> subs;
+    {
+        const int permille_env = env_int("DYNAMIX_TAIL_PERMILLE", -1);
+        const int64_t permille = permille_env >= 0 ? std::min(permille_env, 500) : kTailPermille;
+        const int64_t shortest = std::max(1, env_int("DYNAMIX_TAIL_MIN", kTailMinTiles));
+        const int64_t min_tiles = permille_env >= 0 ? 4 : kTailMinTilesPerBlock;
+        for (int b = 0; b < L.grid; ++b) {
+            subs.push_back({span_begin[b], b});
+            const int64_t tiles = (span_begin[b + 1] - span_begin[b]) / tile;
+            int64_t rest = tiles >= min_tiles ? tiles * permille / 1000 : 0;
+            if (rest < shortest) continue;
+            int64_t v = span_begin[b] + (tiles - rest) * tile;
+            for (int round = 0; rest > 0; ++round) {
+                const int64_t size = std::max(shortest, rest / 2);
+                const int64_t take = rest < size + shortest ? rest : size;   // no shorter rest
+                subs.push_back({v, -1 - round});
+                v += take * tile;    // (the last one also takes what the span has beyond whole tiles)
+                rest -= take;
+            }
+        }
+    }
+    {
+        const int nsubs = (int)subs.size();
+        std::vector<int64_t> sub_begin(nsubs + 1);
+        for (int i = 0; i < nsubs; ++i) sub_begin[i] = subs[i].begin;
+        sub_begin[nsubs] = nvec;
+        L.block_range.assign(2 * (size_t)L.grid, 0);
+        std::vector<std::pair<int, int32_t>> tail;   // (round, piece)
         const int nseg = S > 0 ? S : 1;
         for (int j = 0; j < nseg; ++j) {
             const int64_t lo = S > 0 ? offsets[j] : 0, hi = S > 0 ? offsets[j + 1] : P;
             const int64_t v_lo = lo / VEC, v_hi = ceil_div(hi, VEC);
-            // blocks whose spans meet [v_lo, v_hi)
-            int b = (int)(std::upper_bound(span_begin.begin(), span_begin.end(), v_lo) -
-                          span_begin.begin()) - 1;
-            for (; b < L.grid && span_begin[b] < v_hi; ++b) {
+            // parts of spans that meet [v_lo, v_hi)
+            int b = (int)(std::upper_bound(sub_begin.begin(), sub_begin.end(), v_lo) -
+                          sub_begin.begin()) - 1;
+            for (; b < nsubs && sub_begin[b] < v_hi; ++b) {
                 // a piece is kept below 2^25 vectors: the kernel addresses the aggregate of a
                 // piece with 32-bit byte offsets (at most 32 bytes of it per vector)
-                const int64_t p_begin = std::max(v_lo, span_begin[b]);
-                const int64_t p_end = std::min(v_hi, span_begin[b + 1]);
+                const int64_t p_begin = std::max(v_lo, sub_begin[b]);
+                const int64_t p_end = std::min(v_hi, sub_begin[b + 1]);
                 for (int64_t v = p_begin; v < p_end; v += kMaxPieceVectors) {
                     Piece pc;
                     pc.v_begin = v;
@@ -175,18 +229,23 @@ void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int
                     pc.v_step = tile;
                     pc.e_lo = std::max(lo, pc.v_begin * VEC);
                     pc.e_hi = std::min(hi, pc.v_end * VEC);
-                    pc.block = b;
+                    pc.block = subs[b].owner;
+                    const int32_t index = (int32_t)L.pieces.size();
                     L.pieces.push_back(pc);
-                    per_block[b] += 1;
+                    if (subs[b].owner >= 0) {
+                        // (segments ascend and so do the parts: a block's pieces are consecutive)
+                        int32_t* r = &L.block_range[2 * (size_t)subs[b].owner];
+                        if (r[1] == 0) r[0] = index;
+                        r[1] = index + 1;
+                    } else {
+                        tail.push_back({-1 - subs[b].owner, index});
+                    }
                 }
             }
         }
-        int32_t acc = 0;
-        for (int b = 0; b < L.grid; ++b) {
-            L.block_first.push_back(acc);
-            acc += per_block[b];
-        }
-        L.block_first.push_back(acc);
+        std::stable_sort(tail.begin(), tail.end(),
+                         [](const auto& x, const auto& y) { return x.first < y.first; });
+        for (const auto& t : tail) L.tail_order.push_back(t.second);
     }
 
     // record 0 folds every piece; record 1 + j the pieces of segment j (consecutive by construction)
@@ -218,19 +277,27 @@ int build_plan(Plan& pl, int S, const int64_t* offsets)
     make_layout(pl.K, pl.dtype, pl.P, S, offsets, max_grid, L);
     pl.grid = L.grid;
     pl.pieces = (int)L.pieces.size();
+    pl.n_tail = (int)L.tail_order.size();
     pl.records = 1 + S;
 
     const int W = 2 * pl.K + 1;
     const size_t o_pieces = 0;
     const size_t o_block = align_up(o_pieces + L.pieces.size() * sizeof(Piece), 256);
-    const size_t o_range = align_up(o_block + L.block_first.size() * sizeof(int32_t), 256);
+    const size_t o_tail = align_up(o_block + L.block_range.size() * sizeof(int32_t), 256);
+    const size_t o_range = align_up(o_tail + L.tail_order.size() * sizeof(int32_t), 256);
     const size_t o_count = align_up(o_range + L.rec_range.size() * sizeof(int32_t), 256);
-    const size_t o_part = align_up(o_count + L.rec_count.size() * sizeof(double), 256);
-    const size_t total = o_part + (size_t)pl.pieces * W * sizeof(double);
+    const size_t o_queue = align_up(o_count + L.rec_count.size() * sizeof(double), 256);
+    const size_t o_part = align_up(o_queue + sizeof(int32_t), 256);
+    // the final reduction shares record 0 among several blocks when it has many pieces
+    pl.slices = pl.pieces >= kMinSlicedPieces ? std::min(kMaxSlices, pl.pieces / kPiecesPerSlice) : 1;
+    const size_t o_slices = align_up(o_part + (size_t)pl.pieces * W * sizeof(double), 256);
+    const size_t total = o_slices + (size_t)pl.slices * W * sizeof(double);
     pl.table_bytes = o_part;
     pl.host.assign(o_part, 0);
     std::memcpy(pl.host.data() + o_pieces, L.pieces.data(), L.pieces.size() * sizeof(Piece));
-    std::memcpy(pl.host.data() + o_block, L.block_first.data(), L.block_first.size() * sizeof(int32_t));
+    std::memcpy(pl.host.data() + o_block, L.block_range.data(), L.block_range.size() * sizeof(int32_t));
+    if (!L.tail_order.empty())
+        std::memcpy(pl.host.data() + o_tail, L.tail_order.data(), L.tail_order.size() * sizeof(int32_t));
     std::memcpy(pl.host.data() + o_range, L.rec_range.data(), L.rec_range.size() * sizeof(int32_t));
     std::memcpy(pl.host.data() + o_count, L.rec_count.data(), L.rec_count.size() * sizeof(double));
 
@@ -241,10 +308,13 @@ int build_plan(Plan& pl, int S, const int64_t* offsets)
     }
     pl.blob = static_cast<char*>(dev);
     pl.d_pieces = reinterpret_cast<const Piece*>(pl.blob + o_pieces);
-    pl.d_block_first = reinterpret_cast<const int32_t*>(pl.blob + o_block);
+    pl.d_block_range = reinterpret_cast<const int32_t*>(pl.blob + o_block);
+    pl.d_tail_order = reinterpret_cast<const int32_t*>(pl.blob + o_tail);
     pl.d_rec_range = reinterpret_cast<const int32_t*>(pl.blob + o_range);
     pl.d_rec_count = reinterpret_cast<const double*>(pl.blob + o_count);
     pl.d_partials = reinterpret_cast<double*>(pl.blob + o_part);
+    pl.d_queue = reinterpret_cast<int32_t*>(pl.blob + o_queue);   // zero in the uploaded image
+    pl.d_slice_sums = reinterpret_cast<double*>(pl.blob + o_slices);
     return DYNAMIX_OK;
 }
 
@@ -344,9 +414,12 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
         fa.b[k] = (double)batch_sizes[k];
     }
     sa.pieces = pl->d_pieces;
-    sa.block_first = pl->d_block_first;
+    sa.block_range = pl->d_block_range;
+    sa.tail_order = pl->d_tail_order;
     sa.out_agg = out_agg;
     sa.partials = pl->d_partials;
+    sa.queue = pl->d_queue;
+    sa.n_tail = pl->n_tail;
     sa.params = params;
     sa.lr = lr;
     sa.wd = weight_decay;
@@ -362,6 +435,9 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     fa.rec_range = pl->d_rec_range;
     fa.rec_count = pl->d_rec_count;
     fa.out_stats = out_stats;
+    fa.queue = pl->d_queue;
+    fa.slice_sums = pl->d_slice_sums;
+    fa.slices = pl->slices;
     fa.K = K;
 
     hipEvent_t* ev = nullptr;

@@ -40,16 +40,22 @@ struct Piece {
     int64_t v_step;
     int64_t e_lo;
     int64_t e_hi;
-    int64_t block;   // owning block (diagnostics only)
+    int64_t block;   // owning block, or -1 - round for a piece of the shared tail (diagnostics only)
 };
 
 struct StreamArgs {
     const void* g[kKMax];        // K device pointers
     float w[kKMax];              // b_k / B, rounded once to fp32
     const Piece* pieces;
-    const int32_t* block_first;  // [grid + 1] first piece of each block
+    const int32_t* block_range;  // [grid][2] first and one-past-last piece of each block
     float* out_agg;              // may be null
     double* partials;            // [pieces][2K+1]: A, n_0..n_{K-1}, d_0..d_{K-1}
+    // The pieces listed in tail_order belong to no block: a block that has finished its own
+    // pieces draws them one at a time by adding 1 to *queue (zero at launch; the final reduction,
+    // which follows every streaming pass on the same stream, sets it back).
+    const int32_t* tail_order;   // [n_tail] piece indices
+    int32_t* queue;
+    int32_t n_tail;
     float* params;               // fused model update: p <- p - lr (G + wd p) in place; else null
     float lr, wd;
     // Non-zero: every worker buffer and the output start at a multiple of 256 bytes, and the
@@ -64,6 +70,9 @@ struct FinalArgs {
     const int32_t* rec_range;    // [records][2]: first and one-past-last piece of each record
     const double* rec_count;     // [records] elements covered
     double* out_stats;           // [records][8 + 2K]
+    int32_t* queue;              // the streaming pass's tail counter, reset here
+    double* slice_sums;          // [slices][2K+1] sums of the ranges record 0 is cut into
+    int32_t slices;              // >= 1 blocks that share record 0
     int32_t K;
 };
 

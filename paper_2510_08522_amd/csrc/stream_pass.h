@@ -169,6 +169,10 @@ __device__ __forceinline__ uint32_t from_acc(uint32_t a)
     asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
     return v;
 }
+// A store offset beyond every piece-wide descriptor (at most 2^30 bytes), also after the few
+// bytes added for the second half of a vector.
+constexpr int kMaskedStore = 0x7fff0000;
+
 template <int K, int DT, int U>
 struct Shape {
     static constexpr int kLW = load_words_for(K);                  // words per lane and load
@@ -198,8 +202,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     __shared__ float wave_part[kWaves][W];
 
     const int tid = threadIdx.x;
-    const int p_first = a.block_first[blockIdx.x];
-    const int p_last = a.block_first[blockIdx.x + 1];
+    const int p_first = a.block_range[2 * blockIdx.x];
+    const int p_last = a.block_range[2 * blockIdx.x + 1];
     // What is written per element: the aggregate G, or, with the fused model update, the new
     // parameter p - lr (G + wd p) over the old one; nothing in statistics-only calls.
     const bool fused = a.params != nullptr;
@@ -210,7 +214,24 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
         return fused ? __builtin_fmaf(neg_lr, __builtin_fmaf(wd, p, g), p) : g;
     };
 
-    for (int p = p_first; p < p_last; ++p) {
+    // The block's own pieces, then pieces of the shared tail for as long as there are any: one
+    // lane draws the next index from the counter and hands it to the others through the LDS (the
+    // barrier that ends every piece keeps the draw apart from the previous read).
+    __shared__ int next_piece;
+    const int n_tail = a.n_tail;
+    bool drawn = false;
+    for (int p = p_first;; ++p) {
+        if (drawn || p >= p_last) {
+            drawn = true;
+            if (n_tail == 0) break;
+            if (tid == 0) {
+                const int q = atomicAdd(a.queue, 1);
+                next_piece = q < n_tail ? a.tail_order[q] : -1;
+            }
+            __syncthreads();
+            p = __builtin_amdgcn_readfirstlane(next_piece);
+            if (p < 0) break;
+        }
         const Piece pc = a.pieces[p];
         float n[K], d[K], A = 0.f;
 #pragma unroll
@@ -391,8 +412,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             // costs more than it gains where the write is a large part of the traffic: below
             // eight workers the tiles stay consecutive (measured: 2 to 4 % slower otherwise).
             constexpr bool kSpread = interleaves(K);
-            constexpr int GS = kSpread ? 4 : 0;          // log2 of the tiles per group
-            constexpr int64_t GROUP = TILE << GS;
             // The chunks only pay when they are whole cache lines, so the groups start at a
             // multiple of 256 vectors (the caller says whether the buffers themselves are aligned;
             // a.spread is zero otherwise, and everything is taken in consecutive tiles); the
@@ -402,6 +421,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             const int pre = spread ? (int)min((int64_t)((-body_begin) & 255), body_vectors) : 0;
             const int has_pre = pre > 0 ? 1 : 0;
             const int64_t groups_begin = body_begin + pre;
+            constexpr int GS = kSpread ? 4 : 0;           // log2 of the tiles per group
+            constexpr int GROUP = (int)TILE << GS;        // vectors per group
             // (tile counts fit 32 bits: a tile is at least 1024 elements)
             const int body_tiles = has_pre + (int)((body_end - groups_begin + TILE - 1) / TILE);
             const int full_groups = spread ? (int)((body_end - groups_begin) / GROUP) : 0;
@@ -413,15 +434,15 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 if (t >= body_tiles) return {body_end, 0};
                 if (t < has_pre) return {body_begin, pre};
                 const int64_t v = groups_begin + (int64_t)((t - has_pre) >> GS) * GROUP;
-                return {v, (int)min(GROUP, body_end - v)};
+                return {v, (int)min((int64_t)GROUP, body_end - v)};
             };
             // the vector, counted from where(t).v, that this lane handles as its u-th of tile t
             auto lane_vec_of = [&](int lane, int t, int u) -> int {
                 const int tq = t - has_pre;   // -1 for the short tile in front
                 if (kSpread && tq >= 0 && (tq >> GS) < full_groups) {
-                    const int i = tq & 15;
+                    const int i = tq & ((1 << GS) - 1);
                     const int unit = lane >> 4;
-                    return ((u * 16 + unit) * 16 + ((i + unit) & 15)) * 16 + (lane & 15);
+                    return ((((u * 16 + unit) << GS) + ((i + unit) & ((1 << GS) - 1))) << 4) + (lane & 15);
                 }
                 const int i = tq < 0 ? 0 : tq & ((1 << GS) - 1);
                 return (i * U + u) * kBlock + lane;
@@ -511,8 +532,11 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                             out, body_begin * (VEC * 4), (int)(body_vectors * (VEC * 4)));
                         auto out_off = [&](int tj, int u) -> int {
                             const int tq = tj - has_pre;
-                            const int first = tq < 0 ? 0 : pre + (tq >> GS) * (int)GROUP;
-                            return (first + lane_vec_of(lane_f, tj, u)) * (VEC * 4);
+                            const int lv = lane_vec_of(lane_f, tj, u);
+                            // (the short tile in front ends inside the piece, where this
+                            // descriptor does not: its idle lanes are masked here)
+                            if (tq < 0) return lv < pre ? lv * (VEC * 4) : kMaskedStore;
+                            return (pre + (tq >> GS) * GROUP + lv) * (VEC * 4);
                         };
                         if constexpr (kMode == 1 || kMode == 2) {
 #pragma unroll

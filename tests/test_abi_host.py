@@ -121,9 +121,12 @@ def check_cover(K, P, dtype, off, max_blocks):
     tile = 256 * unroll_for(K)                              # vectors per block iteration
     pcs = D.dynamix_plan_describe(K, P, dtype, off, max_blocks)
     assert len(pcs) >= 1
-    assert (np.diff(pcs[:, 5]) >= 0).all()                      # pieces sorted by owning block
-    assert pcs[:, 5].max() < max_blocks
-    assert set(pcs[:, 5].tolist()) == set(range(int(pcs[:, 5].max()) + 1))   # no idle block index
+    own = pcs[pcs[:, 5] >= 0]                                   # pieces that belong to a block
+    assert pcs[0, 5] == 0                                       # (the rest: the shared tail)
+    assert (np.diff(own[:, 5]) >= 0).all()                      # pieces sorted by owning block
+    assert own[:, 5].max() < max_blocks
+    assert set(own[:, 5].tolist()) == set(range(int(own[:, 5].max()) + 1))   # no idle block index
+    assert (np.diff(pcs[:, 3]) > 0).all()                       # and all of them by position
     cover = np.zeros(P, dtype=np.int32)
     for vb, ve, step, elo, ehi, _ in pcs.tolist():
         assert 0 <= vb < ve and step == tile
@@ -164,8 +167,10 @@ def test_plan_covers_every_element_once(dtype):
 
 def test_plan_for_the_headline_shape_is_balanced():
     pcs = check_cover(32, 138_000_000, 0, None, 256)
-    tiles = -(-(pcs[:, 1] - pcs[:, 0]) // 256)
-    assert len(pcs) == 256                                       # one piece per compute unit
+    own = pcs[pcs[:, 5] >= 0]
+    assert len(own) == 256                                       # one span per compute unit
+    spans = np.diff(np.append(own[:, 0], pcs[-1, 1]))           # (a block's part and its tail pieces)
+    tiles = -(-spans // 256)
     assert tiles.max() - tiles.min() <= 1
 
 
@@ -181,10 +186,44 @@ def test_spans_start_on_wave_boundaries_and_small_inputs_use_every_unit():
     assert len(check_cover(4, 4_096, 0, None, 256)) == 2
 
 
+def test_long_spans_end_in_shared_tail_pieces(monkeypatch):
+    """The last 3 % of every long span belong to no block: they are cut into ever shorter
+    pieces, down to two tiles, which any block draws when its own part is done."""
+    K, P, tile, grid = 32, 138_000_000, 256, 256
+    pcs = check_cover(K, P, 0, None, grid)
+    own = pcs[:, 5] >= 0
+    assert own.sum() == grid
+    n = (pcs[:, 1] - pcs[:, 0])
+    starts = np.where(own)[0]
+    for b in (0, 1, 100, 255):
+        mine = pcs[starts[b]:(starts[b + 1] if b + 1 < grid else len(pcs))]
+        tiles = int((mine[-1, 1] - mine[0, 0]) // tile)          # 526 or 527 (the last: 525 and a rest)
+        assert tiles in (525, 526, 527)
+        sizes = (mine[:, 1] - mine[:, 0]) // tile
+        assert sizes.tolist() == [tiles - 15, 7, 4, 2, 2]      # each half of what is left
+        assert mine[:, 5].tolist() == [b, -1, -2, -3, -4]        # the round in which it is drawn
+        assert (mine[1:, 0] % tile == 0).all()
+    assert pcs[-1, 1] == -(-P // 4)
+    # short inputs have none; the environment can force or forbid one
+    assert (check_cover(K, 256 * 60 * 1024, 0, None, 256)[:, 5] >= 0).all()
+    monkeypatch.setenv("DYNAMIX_TAIL_PERMILLE", "0")
+    assert (check_cover(K, P, 0, None, 256)[:, 5] >= 0).all()
+    monkeypatch.setenv("DYNAMIX_TAIL_PERMILLE", "250")
+    rng = np.random.default_rng(8)
+    for K, P, dtype, mb in [(4, 1_000_003, 0, 16), (16, 3_000_001, 1, 7), (33, 999_999, 2, 5),
+                            (64, 300_001, 0, 3), (8, 5_000_000, 0, 1)]:
+        pcs = check_cover(K, P, dtype, None, mb)
+        assert mb <= (pcs[:, 5] < 0).sum() <= 12 * mb            # halving: few pieces per span
+        cuts = np.sort(rng.choice(np.arange(1, P), size=37, replace=False))
+        pcs = check_cover(K, P, dtype, [0] + [int(c) for c in cuts] + [P], mb)
+        assert (pcs[:, 5] < 0).sum() >= mb
+
+
 def test_long_spans_are_cut_into_pieces_the_kernel_can_address():
     # the kernel addresses the aggregate of a piece with 32-bit byte offsets: 2^25 vectors at most
     pcs = check_cover(64, (1 << 26) + 5, 0, None, 1)
-    assert len(pcs) == 3 and (pcs[:, 1] - pcs[:, 0]).max() == 1 << 25
+    assert (pcs[:, 5] >= 0).sum() == 2 and (pcs[:, 1] - pcs[:, 0]).max() == 1 << 25
+    assert len(pcs) < 40                                         # the tail: a piece per halving
     pcs = check_cover(64, (1 << 26) + 5, 0, [0, 7, (1 << 25) + 9, (1 << 26) + 5], 2)
     assert (pcs[:, 1] - pcs[:, 0]).max() <= 1 << 25
 

@@ -136,6 +136,7 @@ def test_tile_counts_around_the_staging_phases(oracle_mod, monkeypatch, K, dtype
     at and just above each hand-over (LDS full -> first register bank -> second bank -> flush),
     with a ragged last tile."""
     monkeypatch.setenv("DYNAMIX_MAX_BLOCKS", "1")
+    monkeypatch.setenv("DYNAMIX_TAIL_PERMILLE", "0")       # the one block walks all of it in order
     vec = (4 if K <= 32 else 2) * (1 if dtype == torch.float32 else 2)   # elements per vector
     tile = 256 * U * vec                                   # elements per block iteration
     cycle = 2 * NB + NB2
@@ -189,6 +190,55 @@ def test_interleaved_tile_order(oracle_mod, monkeypatch, K, dtype, U, blocks):
     assert all(g.data_ptr() % 256 == 16 for g in w.grads)
     agg1, st1 = run_gpu(w)
     assert np.array_equal(agg, agg1) and np.array_equal(st0, st1)
+
+
+DTYPE_CODE = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
+
+
+@pytest.mark.parametrize("K,dtype,U,vec", [(32, torch.float32, 1, 4), (8, torch.float32, 4, 4),
+                                            (16, torch.bfloat16, 2, 8), (2, torch.float16, 8, 8),
+                                            (40, torch.float32, 1, 2), (64, torch.bfloat16, 1, 2)])
+def test_shared_tail_pieces(oracle_mod, monkeypatch, K, dtype, U, vec):
+    """The end of a long input is cut into short pieces that the blocks draw from a counter (here
+    forced on a short input: a quarter of it, eight blocks).  Which block takes which piece varies
+    from launch to launch; the results may not: every piece yields its own partial record."""
+    monkeypatch.setenv("DYNAMIX_MAX_BLOCKS", "8")
+    monkeypatch.setenv("DYNAMIX_TAIL_PERMILLE", "250")
+    tile = 256 * U * vec
+    rng = np.random.default_rng(61 + K)
+    P = (8 * 40 + 3) * tile - 5
+    cuts = sorted({int(c) for c in rng.integers(1, P, size=6)} | {P - 3 * tile - 7, P - 9})
+    off = [0] + cuts + [P]
+    pcs = D.dynamix_plan_describe(K, P, DTYPE_CODE[dtype], off, 8)
+    assert (pcs[:, 5] < 0).sum() >= 16 and (pcs[:, 5] >= 0).sum() >= 8
+    sig = np.exp(rng.uniform(np.log(1e-3), np.log(1e-1), size=len(off) - 1))
+    w = W.make(K, P, dtype, rng.integers(8, 1025, size=K), 1e-3, sig, seed=70 + K, device=DEV,
+               segment_offsets=off, one_allocation=False)
+    agg, st, _, _ = check(oracle_mod, w, "shared tail K=%d" % K)
+    for rep in range(3):
+        agg2, st2 = run_gpu(w)
+        assert np.array_equal(agg, agg2) and np.array_equal(st, st2), rep
+    _, st3 = run_gpu(w, stats_only=True)
+    assert np.array_equal(st, st3)
+
+
+def test_final_reduction_shared_by_several_blocks(oracle_mod, monkeypatch):
+    """With some hundred pieces record 0 is folded by several blocks, the last of which to finish
+    adds their sums in a fixed order: same bits in every launch, whichever block that is."""
+    monkeypatch.setenv("DYNAMIX_MAX_BLOCKS", "64")
+    monkeypatch.setenv("DYNAMIX_TAIL_PERMILLE", "250")
+    K, tile = 32, 1024
+    P = 64 * 100 * tile + 777
+    off = [0, 5, 13 * tile + 1, 1000 * tile - 3, 5200 * tile + 2, P]
+    assert len(D.dynamix_plan_describe(K, P, 0, off, 64)) >= 4 * 96     # four blocks for record 0
+    rng = np.random.default_rng(123)
+    w = W.make(K, P, torch.float32, rng.integers(8, 1025, size=K), 1e-3,
+               [1e-2, 2e-2, 5e-3, 1e-2, 3e-2], seed=321, device=DEV, segment_offsets=off,
+               one_allocation=False)
+    agg, st, _, _ = check(oracle_mod, w, "final reduction in slices")
+    for rep in range(6):
+        _, st2 = run_gpu(w, stats_only=True)
+        assert np.array_equal(st, st2), rep
 
 
 def test_many_one_element_segments(oracle_mod):
@@ -356,10 +406,14 @@ def test_buffers_allocated_one_by_one(oracle_mod):
     check(oracle_mod, w2, "separate allocations")
 
 
-def test_steady_state_call_can_be_captured_in_a_graph(oracle_mod):
+def test_steady_state_call_can_be_captured_in_a_graph(oracle_mod, monkeypatch):
     # once its plan exists, a call only launches kernels: it can be recorded into a HIP graph and
     # replayed; every replay is checked against an eager call on the same (changed) inputs
-    w = W.config("C1", device=DEV, P=300_001)
+    # (with a shared tail, so that the replays also depend on its counter being set back)
+    monkeypatch.setenv("DYNAMIX_MAX_BLOCKS", "16")
+    monkeypatch.setenv("DYNAMIX_TAIL_PERMILLE", "250")
+    w = W.config("C1", device=DEV, P=3_000_001)
+    assert (D.dynamix_plan_describe(w.K, w.P, 0, None, 16)[:, 5] < 0).sum() >= 16
     out_agg = torch.empty(w.P, dtype=torch.float32, device=DEV)
     out_st = torch.empty((1, HEAD + 2 * w.K), dtype=torch.float64, device=DEV)
     side = torch.cuda.Stream()

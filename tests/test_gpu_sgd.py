@@ -54,12 +54,26 @@ def test_fused_sgd_across_the_staging_phases(oracle_mod, monkeypatch, one_alloca
     """One block, enough tiles to fill the LDS and both register banks more than once, so that
     updated parameters pass through every staging place before they are written."""
     monkeypatch.setenv("DYNAMIX_MAX_BLOCKS", "1")
+    monkeypatch.setenv("DYNAMIX_TAIL_PERMILLE", "0")
     rng = np.random.default_rng(9)
     for K, dtype, tiles, tile in [(32, torch.float32, 2 * 102 + 38 + 3, 1024),
                                   (8, torch.bfloat16, 2 * 25 + 9 + 2, 256 * 4 * 8)]:
         w = W.make(K, tiles * tile - 5, dtype, rng.integers(8, 1025, size=K), 1e-3, 1e-2,
                    seed=600 + K, device=DEV, one_allocation=one_allocation)
         check_step(oracle_mod, w, lr=0.1, wd=5e-4, where="sgd phases K=%d" % K)
+
+
+def test_fused_sgd_with_shared_tail_pieces(oracle_mod, monkeypatch):
+    monkeypatch.setenv("DYNAMIX_MAX_BLOCKS", "8")
+    monkeypatch.setenv("DYNAMIX_TAIL_PERMILLE", "250")
+    rng = np.random.default_rng(10)
+    for K, dtype, tile in [(32, torch.float32, 1024), (8, torch.bfloat16, 256 * 4 * 8)]:
+        P = (8 * 40 + 2) * tile - 3
+        assert (D.dynamix_plan_describe(K, P, 0 if dtype == torch.float32 else 1, None, 8)[:, 5]
+                < 0).sum() >= 16
+        w = W.make(K, P, dtype, rng.integers(8, 1025, size=K), 1e-3, 1e-2, seed=640 + K,
+                   device=DEV, one_allocation=False)
+        check_step(oracle_mod, w, lr=0.1, wd=5e-4, where="sgd shared tail K=%d" % K)
 
 
 def test_fused_sgd_with_segments(oracle_mod):
