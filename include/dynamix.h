@@ -206,6 +206,11 @@ int     dynamix_timing_read(int32_t index, float* stream_pass_ms, float* final_r
  * testing aid: results do not depend on it beyond the order of the fp64 partial sums.
  * DYNAMIX_SPREAD=0 keeps the streaming pass on consecutive tiles also where it would interleave
  * chunks (see `grads` above); read at every call; same kind of aid.
+ * DYNAMIX_TAIL_PERMILLE=n (0..500) sets the share of every block's span that is cut into short
+ * pieces for whichever block is free (default 30, for spans of 64 block iterations or more; 0
+ * turns it off) and DYNAMIX_TAIL_MIN=n the length of the shortest of them in block iterations
+ * (default 2); read when a plan is built; same kind of aid: every piece yields its own partial
+ * sums, so results do not depend on which block took which.
  */
 
 /* Frees every cached plan and workspace.  The caller must have synchronised all streams that
