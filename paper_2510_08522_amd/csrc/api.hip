@@ -444,8 +444,12 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     if (g_timing.used < g_timing.capacity) ev = &g_timing.events[3 * (size_t)g_timing.used++];
     if (ev && hipEventRecord(ev[0], stream) != hipSuccess) return DYNAMIX_ERR_HIP;
     if (launch_stream_pass(K, dtype, pl->grid, sa, stream) != hipSuccess) return DYNAMIX_ERR_HIP;
+    // From here on the tail counter is in use; only the final reduction sets it back.  Should
+    // that not get enqueued, the tables (with a zero counter) are uploaded again next time.
+    pl->uploaded = false;
     if (ev && hipEventRecord(ev[1], stream) != hipSuccess) return DYNAMIX_ERR_HIP;
     if (launch_final_reduce(pl->records, fa, stream) != hipSuccess) return DYNAMIX_ERR_HIP;
+    pl->uploaded = true;
     if (ev && hipEventRecord(ev[2], stream) != hipSuccess) return DYNAMIX_ERR_HIP;
     return DYNAMIX_OK;
 }
