@@ -222,6 +222,26 @@ def test_shared_tail_pieces(oracle_mod, monkeypatch, K, dtype, U, vec):
     assert np.array_equal(st, st3)
 
 
+@pytest.mark.parametrize("K,U", [(8, 4), (32, 1)])
+def test_pieces_that_start_off_the_group_boundaries(oracle_mod, K, U):
+    """Many segments that start at odd elements: each piece first takes the vectors up to the next
+    multiple of 256 as a short tile of its own, whose idle lanes may neither read nor write (the
+    flush addresses the whole piece through one descriptor).  A stray write would race with the
+    real one, so the aggregate is also compared over repeated launches."""
+    tile = 256 * U * 4
+    rng = np.random.default_rng(91 + K)
+    sizes = rng.integers(17 * tile, 40 * tile, size=60) + rng.integers(1, 1000, size=60)
+    off = [0] + [int(x) for x in np.cumsum(sizes)]
+    P = off[-1]
+    w = W.make(K, P, torch.float32, rng.integers(8, 1025, size=K), 1e-3,
+               np.full(60, 1e-2), seed=17 + K, device=DEV, segment_offsets=off,
+               one_allocation=False)
+    agg, st, _, _ = check(oracle_mod, w, "short tiles in front K=%d" % K)
+    for rep in range(5):
+        agg2, st2 = run_gpu(w)
+        assert np.array_equal(agg, agg2) and np.array_equal(st, st2), rep
+
+
 def test_final_reduction_shared_by_several_blocks(oracle_mod, monkeypatch):
     """With some hundred pieces record 0 is folded by several blocks, the last of which to finish
     adds their sums in a fixed order: same bits in every launch, whichever block that is."""
