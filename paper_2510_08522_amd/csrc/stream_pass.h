@@ -149,8 +149,8 @@ __device__ __forceinline__ void stagger_waves(int tid)
 // and, up to K = 44, the 256 accumulation registers of every lane: when the LDS is full for the
 // first time in a flush cycle every lane moves its own slots into a first bank of registers,
 // when it is full again (as far as the remaining registers reach) into a second, and after the
-// third filling everything is written out.  A lane reads back only what it wrote, so the moves
-// need no synchronisation.
+// third filling everything is written out.  With fp32 inputs a lane reads back only what it
+// wrote, so the moves need no synchronisation (16-bit inputs: see kSwap in the kernel).
 constexpr int kStageBytes = 152 * 1024;
 
 // The banks live in the accumulation half of the register file, which nothing else in this
@@ -480,6 +480,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             uint32_t bank2[(NB2 > 0 ? NB2 : 1) * U * Q * LW];
             int t_bank = 0, t_bank2 = 0;   // first tile of each bank
             bool more = true;
+            // 16-bit inputs: a vector of G is twice the width of a store, and a lane that wrote
+            // its own two halves would leave every store instruction with gaps of its own width
+            // between the lanes.  The h-th store of a lane therefore takes one half of another
+            // lane's vector, so that the 256 lanes of an instruction write 256 consecutive
+            // pieces: lane l stores half (l mod 2) of the vector that lane 128 h + l / 2 parked.
+            // The data change lanes in the LDS, between the barriers of the flush or, for the
+            // register banks, when the banks are filled (with barriers of their own).
+            constexpr bool kSwap = Q == 2;
+            auto src_lane = [&](int lane, int h) -> int {
+                return kSwap ? h * (kBlock / 2) + (lane >> 1) : lane;
+            };
+            auto src_half = [&](int lane, int h) -> int { return kSwap ? (lane & 1) : h; };
             // One tile.  With the bank the loop over tiles exists twice (two instantiations of this
             // body): once for the first half of a flush cycle, while the bank is empty, and once
             // for the second half, during which the bank is only kept, never redefined, so that
@@ -500,7 +512,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 for (int u = 0; u < U; ++u) {
                     pass1(x[u], G[u]);
                     if (want_agg) {
-                        // park G; every thread later reads back only what it wrote itself
+                        // park G (fp32 inputs: every thread later reads back only what it wrote
+                        // itself; 16-bit inputs: see kSwap)
 #pragma unroll
                         for (int h = 0; h < Q; ++h) {
                             wvec q;
@@ -530,13 +543,15 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                         // 2^25 vectors, so byte offsets inside it fit the 32-bit lane offset)
                         const __amdgpu_buffer_rsrc_t r = tile_rsrc(
                             out, body_begin * (VEC * 4), (int)(body_vectors * (VEC * 4)));
-                        auto out_off = [&](int tj, int u) -> int {
+                        // where this lane's h-th store of a tile goes (see kSwap)
+                        auto out_off = [&](int tj, int u, int h) -> int {
                             const int tq = tj - has_pre;
-                            const int lv = lane_vec_of(lane_f, tj, u);
+                            const int lv = lane_vec_of(src_lane(lane_f, h), tj, u);
+                            const int in_vec = VB * src_half(lane_f, h);
                             // (the short tile in front ends inside the piece, where this
                             // descriptor does not: its idle lanes are masked here)
-                            if (tq < 0) return lv < pre ? lv * (VEC * 4) : kMaskedStore;
-                            return (pre + (tq >> GS) * GROUP + lv) * (VEC * 4);
+                            if (tq < 0) return lv < pre ? lv * (VEC * 4) + in_vec : kMaskedStore;
+                            return (pre + (tq >> GS) * GROUP + lv) * (VEC * 4) + in_vec;
                         };
                         if constexpr (kMode == 1 || kMode == 2) {
 #pragma unroll
@@ -551,8 +566,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #pragma unroll
                                         for (int c = 0; c < LW; ++c)
                                             t[c] = from_acc(bank[((j * U + u) * Q + h) * LW + c]);
-                                        Wd::template store<kStorePolicy>(
-                                            t, r, out_off(tj, u) + VB * h);
+                                        Wd::template store<kStorePolicy>(t, r, out_off(tj, u, h));
                                     }
                             }
                         }
@@ -569,8 +583,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #pragma unroll
                                         for (int c = 0; c < LW; ++c)
                                             t[c] = from_acc(bank2[((j * U + u) * Q + h) * LW + c]);
-                                        Wd::template store<kStorePolicy>(
-                                            t, r, out_off(tj, u) + VB * h);
+                                        Wd::template store<kStorePolicy>(t, r, out_off(tj, u, h));
                                     }
                             }
                         }
@@ -581,8 +594,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #pragma unroll
                                 for (int h = 0; h < Q; ++h)
                                     Wd::template store<kStorePolicy>(
-                                        stage[(j * U + u) * Q + h][tid], r,
-                                        out_off(tj, u) + VB * h);
+                                        stage[(j * U + u) * Q + src_half(tid, h)][src_lane(tid, h)],
+                                        r, out_off(tj, u, h));
                         }
                         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                         __syncthreads();
@@ -630,12 +643,20 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                     tile_body(std::integral_constant<int, 0>{});
                 } while (more && staged < NB);
                 if (!more) break;
-                // every lane moves its own slots into the first bank, and the LDS fills again
+                // every lane moves the slots it will store into the first bank, and the LDS fills
+                // again
+                if (kSwap) __syncthreads();
 #pragma unroll
-                for (int j = 0; j < NB * U * Q; ++j) {
-                    const wvec t = stage[j][tid];
+                for (int j = 0; j < NB * U; ++j)
 #pragma unroll
-                    for (int c = 0; c < LW; ++c) bank[j * LW + c] = to_acc(t[c]);
+                    for (int h = 0; h < Q; ++h) {
+                        const wvec t = stage[j * Q + src_half(tid, h)][src_lane(tid, h)];
+#pragma unroll
+                        for (int c = 0; c < LW; ++c) bank[(j * Q + h) * LW + c] = to_acc(t[c]);
+                    }
+                if (kSwap) {
+                    __syncthreads();
+                    if (long_run) stagger_waves(tid);
                 }
                 t_bank = t_staged;
                 staged = 0;
@@ -645,11 +666,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                     } while (more && staged < NB2);
                     if (!more) break;
                     // the second, smaller bank
+                    if (kSwap) __syncthreads();
 #pragma unroll
-                    for (int j = 0; j < NB2 * U * Q; ++j) {
-                        const wvec t = stage[j][tid];
+                    for (int j = 0; j < NB2 * U; ++j)
 #pragma unroll
-                        for (int c = 0; c < LW; ++c) bank2[j * LW + c] = to_acc(t[c]);
+                        for (int h = 0; h < Q; ++h) {
+                            const wvec t = stage[j * Q + src_half(tid, h)][src_lane(tid, h)];
+#pragma unroll
+                            for (int c = 0; c < LW; ++c) bank2[(j * Q + h) * LW + c] = to_acc(t[c]);
+                        }
+                    if (kSwap) {
+                        __syncthreads();
+                        if (long_run) stagger_waves(tid);
                     }
                     t_bank2 = t_staged;
                     staged = 0;
