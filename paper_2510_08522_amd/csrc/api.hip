@@ -97,7 +97,12 @@ int env_int(const char* name, int fallback)
 
 // The work decomposition (pure host arithmetic, no HIP): pieces, the pieces of every block, the
 // order of the shared tail, and per record its piece range and element count.
-constexpr int64_t kMaxPieceVectors = (int64_t)1 << 25;   // a multiple of every tile size
+// Longest piece, a multiple of every tile size.  Two reasons: the kernel addresses the aggregate
+// of a piece with 32-bit byte offsets (2^25 vectors would still do), and a lane adds the squares of
+// a piece in fp32 before they reach the fp64 partial sums, with an error that grows with their
+// number (measured with fp16 inputs: 2e-5 relative after 121 000 elements per lane, 7e-6 after
+// 32 000, 3e-7 after 500); 2^18 vectors are at most 8 192 elements per lane.
+constexpr int64_t kMaxPieceVectors = (int64_t)1 << 18;
 constexpr int kTailPermille = 30;           // share of the range that goes to the shared tail
 constexpr int kMaxSlices = 16;              // blocks of the final reduction that share record 0
 constexpr int kPiecesPerSlice = 96;         // ... one per that many pieces, from kMinSlicedPieces on
@@ -218,8 +223,7 @@ void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int
             int b = (int)(std::upper_bound(sub_begin.begin(), sub_begin.end(), v_lo) -
                           sub_begin.begin()) - 1;
             for (; b < nsubs && sub_begin[b] < v_hi; ++b) {
-                // a piece is kept below 2^25 vectors: the kernel addresses the aggregate of a
-                // piece with 32-bit byte offsets (at most 32 bytes of it per vector)
+                // (no piece longer than kMaxPieceVectors)
                 const int64_t p_begin = std::max(v_lo, sub_begin[b]);
                 const int64_t p_end = std::min(v_hi, sub_begin[b + 1]);
                 for (int64_t v = p_begin; v < p_end; v += kMaxPieceVectors) {

@@ -540,7 +540,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                         int lane_f = tid;
                         asm volatile("" : "+v"(lane_f));
                         // one descriptor over the whole body for the stores (a piece has at most
-                        // 2^25 vectors, so byte offsets inside it fit the 32-bit lane offset)
+                        // 2^18 vectors, so byte offsets inside it fit the 32-bit lane offset)
                         const __amdgpu_buffer_rsrc_t r = tile_rsrc(
                             out, body_begin * (VEC * 4), (int)(body_vectors * (VEC * 4)));
                         // where this lane's h-th store of a tile goes (see kSwap)

@@ -219,13 +219,17 @@ def test_long_spans_end_in_shared_tail_pieces(monkeypatch):
         assert (pcs[:, 5] < 0).sum() >= mb
 
 
-def test_long_spans_are_cut_into_pieces_the_kernel_can_address():
-    # the kernel addresses the aggregate of a piece with 32-bit byte offsets: 2^25 vectors at most
-    pcs = check_cover(64, (1 << 26) + 5, 0, None, 1)
-    assert (pcs[:, 5] >= 0).sum() == 2 and (pcs[:, 1] - pcs[:, 0]).max() == 1 << 25
+def test_long_spans_are_cut_into_pieces_of_bounded_length():
+    # a lane adds a piece's squares in fp32 before they reach the fp64 partial sums, and the kernel
+    # addresses the aggregate of a piece with 32-bit byte offsets: 2^18 vectors at most
+    P = (1 << 20) + 5
+    pcs = check_cover(64, P, 0, None, 1)
+    assert (pcs[:, 1] - pcs[:, 0]).max() == 1 << 18 and (pcs[:, 5] >= 0).sum() == 4
     assert len(pcs) < 40                                         # the tail: a piece per halving
-    pcs = check_cover(64, (1 << 26) + 5, 0, [0, 7, (1 << 25) + 9, (1 << 26) + 5], 2)
-    assert (pcs[:, 1] - pcs[:, 0]).max() <= 1 << 25
+    pcs = check_cover(64, P, 0, [0, 7, (1 << 19) + 9, P], 2)
+    assert (pcs[:, 1] - pcs[:, 0]).max() <= 1 << 18
+    pcs = check_cover(4, (1 << 22) + 77, 1, None, 1)             # 8 elements per vector
+    assert (pcs[:, 1] - pcs[:, 0]).max() == 1 << 18
 
 
 def test_plan_describe_rejects_bad_shapes():
