@@ -97,6 +97,7 @@ int env_int(const char* name, int fallback)
 
 // The work decomposition (pure host arithmetic, no HIP): pieces, the pieces of every block, the
 // order of the shared tail, and per record its piece range and element count.
+
 // Longest piece, a multiple of every tile size.  Two reasons: the kernel addresses the aggregate
 // of a piece with 32-bit byte offsets (2^25 vectors would still do), and a lane adds the squares of
 // a piece in fp32 before they reach the fp64 partial sums, with an error that grows with their
