@@ -52,24 +52,46 @@ def _bank_registers(K, dtype, U):
 
 
 def _check_resources(remarks, src):
-    """The streaming pass must not spill and must not have values moved into accumulation
-    registers by the compiler (instantiations built that way have returned wrong sums on gfx950);
-    the only accumulation registers allowed are those of its explicit bank."""
-    name, bad = None, []
+    """The streaming pass must not spill vector registers and must not have values moved into
+    accumulation registers by the compiler (instantiations built that way have returned wrong
+    sums on gfx950); the only accumulation registers allowed are those of its explicit bank.
+    Returns the kernels that reserve a private segment without spilling a vector register (the
+    compiler sometimes keeps an unused slot per register that carries spilled scalars): their
+    code has to be looked at, see _uses_scratch."""
+    name, bad, reserved = None, [], []
+    scratch = {}
     for line in remarks.splitlines():
         if "Function Name:" in line:
             m = _KERNEL.search(line)
             name = tuple(int(x) for x in m.groups()) if m else None
         elif name is not None:
-            m = re.search(r"remark:\s+(AGPRs|ScratchSize \[bytes/lane\]): (\d+)", line)
-            if m and m.group(1) == "AGPRs" and int(m.group(2)) != _bank_registers(*name):
-                bad.append("K=%d dtype=%d: %s accumulation registers, expected %d"
-                           % (name[0], name[1], m.group(2), _bank_registers(*name)))
-            if m and m.group(1).startswith("Scratch") and int(m.group(2)) != 0:
-                bad.append("K=%d dtype=%d: %s bytes of scratch" % (name[0], name[1], m.group(2)))
+            m = re.search(r"remark:\s+(AGPRs|ScratchSize \[bytes/lane\]|VGPRs Spill): (\d+)", line)
+            if not m:
+                continue
+            what, value = m.group(1), int(m.group(2))
+            if what == "AGPRs" and value != _bank_registers(*name):
+                bad.append("K=%d dtype=%d: %d accumulation registers, expected %d"
+                           % (name[0], name[1], value, _bank_registers(*name)))
+            elif what.startswith("Scratch") and value != 0:
+                scratch[name] = value
+            elif what == "VGPRs Spill" and value != 0:
+                bad.append("K=%d dtype=%d: %d vector registers spilled" % (name[0], name[1], value))
+    spilled = {b.split(":")[0] for b in bad if "spilled" in b}
+    for name, value in scratch.items():
+        if "K=%d dtype=%d" % name[:2] in spilled:
+            bad.append("K=%d dtype=%d: %d bytes of scratch" % (name[0], name[1], value))
+        else:
+            reserved.append(name)
     if bad:
         raise RuntimeError("register allocation of %s is not as required:\n  %s"
                            % (os.path.basename(src), "\n  ".join(bad)))
+    return reserved
+
+
+def _uses_scratch(assembly):
+    """Whether generated code (text, as written by hipcc -S for gfx950, where every access to the
+    private segment is a scratch_ instruction) touches the private segment."""
+    return re.search(r"^\s+scratch_", assembly, re.MULTILINE) is not None
 
 
 def _compile(job):
@@ -83,7 +105,20 @@ def _compile(job):
     if r.returncode != 0:
         raise RuntimeError("hipcc failed: %s\n%s" % (" ".join(cmd), "\n".join(lines)))
     if check:
-        _check_resources(r.stdout, src)
+        reserved = _check_resources(r.stdout, src)
+        if reserved:
+            # a private segment without a spilled vector register: the code must not touch it
+            asm = obj[:-2] + ".s"
+            a = subprocess.run([HIPCC] + FLAGS + defs + ["-S", "--cuda-device-only", src, "-o", asm],
+                               stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+            if a.returncode != 0:
+                raise RuntimeError("hipcc -S failed for %s" % src)
+            with open(asm) as fh:
+                text = fh.read()
+            os.remove(asm)
+            if _uses_scratch(text):
+                raise RuntimeError("register allocation of %s is not as required: scratch is "
+                                   "accessed (K, dtype, unroll: %s)" % (os.path.basename(src), reserved))
         lines = [l for l in lines if "remark:" not in l and "Rpass-analysis" not in l]
     return "\n".join(lines)
 

@@ -238,12 +238,17 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
         for (int k = 0; k < K; ++k) n[k] = d[k] = 0.f;
 
         // pass 1 over the K vectors of one lane: the weighted aggregate, k ascending
-        auto pass1 = [&](const wvec (&xu)[K], float (&Gu)[VEC]) {
+        // With 31 or 32 fp32 workers the K weights and buffer addresses are read from the kernel
+        // arguments again for every tile (scalar loads that hit the scalar cache, at an offset the
+        // compiler cannot see through): kept in scalar registers for the whole loop they push so
+        // many other scalars into spill lanes of vector registers that the loop runs out of those.
+        constexpr bool kReloadWeights = K >= 31 && K <= 32 && DT == kF32;
+        auto pass1 = [&](const wvec (&xu)[K], float (&Gu)[VEC], const float* kw) {
 #pragma unroll
             for (int c = 0; c < VEC; ++c) Gu[c] = 0.f;
 #pragma unroll
             for (int k = 0; k < K; ++k) {
-                const float wk = a.w[k];
+                const float wk = kReloadWeights ? kw[k] : a.w[k];
 #pragma unroll
                 for (int c = 0; c < LW; ++c) {
                     const uint32_t q = xu[k][c];
@@ -474,6 +479,41 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             }
             int staged = 0;            // tiles parked in LDS
             int t_staged = 0;          // first of them
+            // When to flush.  A flush is short (10 us for 400 KB), but what the chip loses to the
+            // writes depends on how they are spread in time: blocks that flush whenever their own
+            // staging is full drift apart (their first flushes already lie 75 us apart, the fifth
+            // 200 us) and the memory sees a steady trickle of writes among the reads; all blocks
+            // flushing within a few microseconds of each other costs a quarter less (C4: 2.70 ->
+            // 2.64 ms).  So the blocks flush at common instants, the multiples of kFlushPeriod on
+            // the device-wide clock, with whatever they have parked by then (and, as before, when
+            // the staging is full or the piece ends).  The four waves of a block have to agree on
+            // the tile after which they flush without meeting: wave 0 reads the clock once per
+            // tile and, when an instant has passed, announces in the LDS "flush after tile t + 2";
+            // it also publishes its progress, and no other wave passes the flush point of a tile
+            // before wave 0 has decided about it, i.e. has been through the tile two before it.
+            // Wave 0 never waits for the others except in barriers that they reach without
+            // waiting for it, so nobody waits for ever.
+            constexpr int kStagedMax = K <= 44 ? 2 * NB + NB2 : NB;
+            // the period: four fifths of the time a block takes to fill its staging at full speed
+            // (a tile at 26.5 GB/s per compute unit), in ticks of the 100 MHz clock
+            constexpr uint32_t kFlushPeriod = (uint32_t)(
+                0.8 * kStagedMax * ((double)(kBlock * U) * (K * VB + VEC * 4) / 265.0));
+            constexpr int kNever = 0x7fffffff;
+            __shared__ int wave0_progress, flush_after;
+            // (only where a piece fills the staging several times: one that fits it once is
+            // better off with its single flush at the end)
+            const bool timed = want_agg && body_vectors >= 2 * kStagedMax * TILE;
+            int announced = kNever;        // wave 0: the tile it has announced a flush after
+            uint32_t next_instant = 0;     // wave 0: clock value of the next common instant
+            if (timed) {
+                if (tid == 0) {
+                    wave0_progress = 0;
+                    flush_after = kNever;
+                }
+                const uint32_t now = (uint32_t)wall_clock64();
+                next_instant = now - now % kFlushPeriod + kFlushPeriod;
+                __syncthreads();
+            }
             // the register banks (accumulation registers): NB and NB2 more tiles, parked before
             // those in the LDS
             uint32_t bank[NB * U * Q * LW];
@@ -506,11 +546,15 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 const int tn = t + 1;
                 const Where wn = where(tn);
                 more = wn.count > 0;
+                uint32_t hidden_zero = 0;
+                if constexpr (kReloadWeights) asm volatile("" : "+s"(hidden_zero));
+                const float* const kw = a.w + hidden_zero;
+                const void* const* const kg = a.g + hidden_zero;   // (likewise the K addresses)
 
                 float G[U][VEC];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    pass1(x[u], G[u]);
+                    pass1(x[u], G[u], kw);
                     if (want_agg) {
                         // park G (fp32 inputs: every thread later reads back only what it wrote
                         // itself; 16-bit inputs: see kSwap)
@@ -532,7 +576,33 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 if (want_agg) {
                     if (staged == 0) t_staged = t;
                     ++staged;
-                    if (kMode <= 1 ? !more : (staged == NB || !more)) {
+                    bool on_time = false;
+                    if (timed) {
+                        if (__builtin_amdgcn_readfirstlane(tid) < 64) {   // wave 0
+                            if (announced == kNever) {
+                                const uint32_t now = (uint32_t)wall_clock64();
+                                if ((int32_t)(now - next_instant) >= 0) {
+                                    announced = t + 2;
+                                    if (tid == 0)
+                                        __hip_atomic_store(&flush_after, announced, __ATOMIC_RELAXED,
+                                                           __HIP_MEMORY_SCOPE_WORKGROUP);
+                                }
+                            }
+                            // (released after the announcement: who sees the progress sees it too)
+                            if (tid == 0)
+                                __hip_atomic_store(&wave0_progress, t + 1, __ATOMIC_RELEASE,
+                                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+                            on_time = t == announced;
+                        } else {
+                            while (__hip_atomic_load(&wave0_progress, __ATOMIC_ACQUIRE,
+                                                     __HIP_MEMORY_SCOPE_WORKGROUP) < t - 1)
+                                __builtin_amdgcn_s_sleep(1);
+                            on_time = __hip_atomic_load(&flush_after, __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_WORKGROUP) == t;
+                        }
+                        on_time = __builtin_amdgcn_readfirstlane((int)on_time) != 0;
+                    }
+                    if (kMode <= 1 ? (!more || on_time) : (staged == NB || !more || on_time)) {
                         __syncthreads();
                         // the store addresses are worked out here, from a copy of the lane number
                         // the compiler cannot see through: otherwise it prepares them ahead of
@@ -600,6 +670,11 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                         __syncthreads();
                         staged = 0;
+                        if (on_time) {
+                            announced = kNever;
+                            const uint32_t now = (uint32_t)wall_clock64();
+                            next_instant = now - now % kFlushPeriod + kFlushPeriod;
+                        }
                         if (long_run) stagger_waves(tid);
                     }
                 }
@@ -617,7 +692,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                         int pf_off = next_vec * VB;
                         asm volatile("" : "+v"(pf_off) : "v"(n[k]), "v"(d[k]));
                         x[u][k] = Wd::template load<kLoadPolicy>(
-                            tile_rsrc(a.g[k], wn.v * VB, next_bytes), pf_off);
+                            tile_rsrc(kReloadWeights ? kg[k] : a.g[k], wn.v * VB, next_bytes), pf_off);
                     }
                 }
                 {
@@ -641,8 +716,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 // until the LDS is full (or the run ends, which flushes)
                 do {
                     tile_body(std::integral_constant<int, 0>{});
-                } while (more && staged < NB);
+                } while (more && staged != 0 && staged < NB);
                 if (!more) break;
+                if (staged == 0) continue;   // flushed on time, before the LDS was full: start again
                 // every lane moves the slots it will store into the first bank, and the LDS fills
                 // again
                 if (kSwap) __syncthreads();
@@ -663,8 +739,9 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 if constexpr (NB2 > 0) {
                     do {
                         tile_body(std::integral_constant<int, 1>{});
-                    } while (more && staged < NB2);
+                    } while (more && staged != 0 && staged < NB2);
                     if (!more) break;
+                    if (staged == 0) continue;
                     // the second, smaller bank
                     if (kSwap) __syncthreads();
 #pragma unroll

@@ -286,12 +286,18 @@ def test_build_check_of_register_allocation():
     tag = "[-Rpass-analysis=kernel-resource-usage]"
     fn = "x.hip:1:1: remark: Function Name: _ZN7dynamix18stream_pass_kernelILi%dELi0ELi1EEEvNS_10StreamArgsE " + tag
 
-    def remarks(K, agprs, scratch):
+    def remarks(K, agprs, scratch, spilled=0):
         return "\n".join([fn % K, "x.hip:1:1: remark:     VGPRs: 246 " + tag,
                           "x.hip:1:1: remark:     AGPRs: %d %s" % (agprs, tag),
-                          "x.hip:1:1: remark:     ScratchSize [bytes/lane]: %d %s" % (scratch, tag)])
-    Bd._check_resources(remarks(32, 256, 0), "x.hip")
-    Bd._check_resources(remarks(50, 0, 0), "x.hip")
-    for bad in (remarks(32, 152, 0), remarks(32, 256, 8), remarks(50, 6, 0)):
+                          "x.hip:1:1: remark:     ScratchSize [bytes/lane]: %d %s" % (scratch, tag),
+                          "x.hip:1:1: remark:     VGPRs Spill: %d %s" % (spilled, tag)])
+    assert Bd._check_resources(remarks(32, 256, 0), "x.hip") == []
+    assert Bd._check_resources(remarks(50, 0, 0), "x.hip") == []
+    for bad in (remarks(32, 152, 0), remarks(32, 256, 8, 1), remarks(50, 6, 0), remarks(8, 256, 0, 2)):
         with pytest.raises(RuntimeError):
             Bd._check_resources(bad, "x.hip")
+    # a private segment that no vector register was spilled to is reported for a look at the code
+    assert Bd._check_resources(remarks(32, 256, 36), "x.hip") == [(32, 0, 1)]
+    assert Bd._uses_scratch("\tv_add_f32 v1, v2, v3\n\tscratch_store_dword off, v249, off\n")
+    assert not Bd._uses_scratch("\tbuffer_store_dwordx4 v[1:4], v5, s[8:11], 0 offen nt\n"
+                                "\t.amdhsa_private_segment_fixed_size 36\n")
