@@ -40,6 +40,17 @@ def describe(w):
     return "%s: K=%d workers, P=%d %s gradients, %s" % (w.name, w.K, w.P, dt, seg)
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(w, sample_elems, threads):
     """Times the CPU oracle, as it stands, on the first `sample_elems` elements of every worker
     buffer (copied to the host outside the timed part)."""
@@ -62,6 +73,7 @@ def cpu_baseline(w, sample_elems, threads):
     oracle.aggregate_stats(host1, w.batch_sizes, off1, want_agg=True, threads=1)
     dt1 = time.perf_counter() - t0
     return {"value": nbytes / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "nproc": os.cpu_count(), "cpu_model": cpu_model(),
             "sample": "first %d of %d elements of each of the %d worker buffers "
                       "(%.3f GB read, %.2f s wall)" % (n, w.P, w.K, nbytes / 1e9, dt),
             "elements_per_s": w.K * n / dt,

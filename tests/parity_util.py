@@ -1,7 +1,7 @@
 """Comparison of the HIP path's outputs with the CPU oracle's, to the stated tolerances.
 
 Tolerances (relative): 1e-5 for the aggregate vector and the squared norms with fp32 inputs,
-1e-3 with bf16 inputs, 1e-4 for the noise scale (1e-3 with bf16 inputs).
+1e-3 with bf16 inputs, 1e-4 for the noise scale whatever the input type.
 
 A vector is compared in the 2-norm and in the max-norm relative to the oracle's largest entry,
 because single entries of a weighted mean can cancel to almost nothing.
@@ -21,7 +21,7 @@ HEAD = 8
 
 
 def tolerances(is_bf16):
-    return (1e-3, 1e-3) if is_bf16 else (1e-5, 1e-4)
+    return (1e-3, 1e-4) if is_bf16 else (1e-5, 1e-4)
 
 
 def compare(agg_gpu, stats_gpu, agg_ref, stats_ref, batch_sizes, is_bf16=False, where=""):
@@ -82,3 +82,13 @@ def compare(agg_gpu, stats_gpu, agg_ref, stats_ref, batch_sizes, is_bf16=False, 
                     assert abs(g[3] - o[3]) <= (tol_ns + slack_u) * abs(o[3]), (tag, "noise_scale", g[3], o[3])
         else:
             assert g[1] == 0.0 and g[3] == 0.0 and g[4] == 0.0 and g[6] == 0.0, tag
+
+
+def compare_sgd(got, ref, p0, agg_ref, lr, is_bf16=False, where=""):
+    """Updated parameters of the fused SGD step against the oracle's: the fp32 evaluation of
+    p - lr (G + wd p) adds two roundings to the aggregate's own error."""
+    tol = 1e-3 if is_bf16 else 1e-5
+    got = np.asarray(got, dtype=np.float64)
+    scale = np.abs(np.asarray(p0, dtype=np.float64)) + abs(lr) * np.abs(agg_ref)
+    assert np.linalg.norm(got - ref) <= tol * np.linalg.norm(ref), where
+    assert (np.abs(got - ref) <= 4e-7 * scale + tol * abs(lr) * np.abs(agg_ref).max()).all(), where

@@ -46,8 +46,10 @@ def test_config_full_size(oracle_mod, name):
 
 
 def test_config_c4_full_size_headline(oracle_mod):
-    # K=32, P=138M fp32: the shape and launch configuration the benchmark times
-    w = W.config("C4", device=DEV)
+    # K=32, P=138M fp32 in K allocations made one by one: the shape, buffer layout and launch
+    # configuration the benchmark times
+    w = W.config("C4", device=DEV, one_allocation=False)
+    assert all(g.data_ptr() % 256 == 0 for g in w.grads)
     _, st, _, _ = check(oracle_mod, w, "C4")
     assert abs(st[0, D.STAT["noise_scale"]] / 100.0 - 1.0) < 0.02
 

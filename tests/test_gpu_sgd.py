@@ -5,7 +5,7 @@ import torch
 
 import paper_2510_08522_amd as D
 from paper_2510_08522_amd import workloads as W
-from parity_util import compare
+from parity_util import compare, compare_sgd
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -26,12 +26,8 @@ def check_step(oracle_mod, w, lr, wd, where):
     ragg, rst = oracle_mod.aggregate_stats(w.host_arrays(), w.batch_sizes, w.segment_offsets,
                                            threads=16)
     ref = oracle_mod.sgd_step(ragg, p0.cpu().numpy(), lr, wd)
-    got = p.cpu().numpy().astype(np.float64)
-    # fp32 evaluation of p - lr (G + wd p): two roundings on top of the aggregate's own error
-    tol = 1e-3 if w.dtype == torch.bfloat16 else 1e-5
-    scale = np.abs(p0.cpu().numpy()).astype(np.float64) + abs(lr) * np.abs(ragg)
-    assert np.linalg.norm(got - ref) <= tol * np.linalg.norm(ref), where
-    assert (np.abs(got - ref) <= 4e-7 * scale + tol * abs(lr) * np.abs(ragg).max()).all(), where
+    compare_sgd(p.cpu().numpy(), ref, p0.cpu().numpy(), ragg, lr,
+                is_bf16=(w.dtype == torch.bfloat16), where=where)
     # the statistics are those of the plain call
     compare(None, st.cpu().numpy(), ragg, rst, w.batch_sizes, is_bf16=(w.dtype == torch.bfloat16),
             where=where)
