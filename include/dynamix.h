@@ -47,10 +47,13 @@ typedef enum {
     DYNAMIX_ERR_SEGMENTS = 3, /* offsets do not start at 0, are not strictly increasing, or do not end at P */
     DYNAMIX_ERR_ALIGN = 4,    /* a gradient pointer or out_agg is not 16-byte aligned, or out_stats not 8-byte */
     DYNAMIX_ERR_NOMEM = 5,    /* the library could not allocate its workspace */
-    DYNAMIX_ERR_HIP = 6       /* a HIP runtime call failed (launch, copy, device query) */
+    DYNAMIX_ERR_HIP = 6,      /* a HIP runtime call failed (launch, copy, device query) */
+    DYNAMIX_ERR_CAPACITY = 7  /* dynamix_grad_aggregate_stats_static: the shape needs more than
+                                 DYNAMIX_STATIC_SCRATCH_BYTES of workspace */
 } dynamix_status;
 
 enum { DYNAMIX_K_MAX = 64 };        /* most workers per call: pointers and weights travel in the kernel arguments */
+enum { DYNAMIX_STATIC_SCRATCH_BYTES = 4 << 20 }; /* workspace of dynamix_grad_aggregate_stats_static */
 enum { DYNAMIX_STATS_HEAD = 8 };    /* scalars in front of the per-worker entries of a record */
 
 /* Positions inside one statistics record of DYNAMIX_STATS_HEAD + 2K doubles. */
@@ -114,6 +117,28 @@ int dynamix_grad_aggregate_stats_ex(const void* const* grads, const int32_t* bat
                                     int32_t K, int64_t P, int32_t dtype,
                                     const int64_t* segment_offsets, int64_t num_segments,
                                     float* out_agg, double* out_stats, void* stream);
+
+/*
+ * dynamix_grad_aggregate_stats_ex for callers that cannot allocate device memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same
+ * kernels, same results bit for bit, but the library's workspace (plan tables, tail counter,
+ * partial sums) lies in a static device array of DYNAMIX_STATIC_SCRATCH_BYTES (4 MiB, held by every
+ * GPU the library runs on until the process ends) instead of an allocation per shape.  The call
+ * makes no hipMalloc, hipFree or other allocating call, not even the first time: the tables reach
+ * the device in kernel arguments, on `stream`.  Returns DYNAMIX_ERR_CAPACITY, before anything is
+ * enqueued, when tables plus partial sums exceed the array: 48 bytes per piece of the work
+ * decomposition (dynamix_plan_describe counts them; about 5 per block plus one per segment) plus
+ * 8 (2K + 1) per piece for its partial sums plus 24 per segment; the paper-sized shapes need
+ * 0.2 to 0.8 MiB, K = 64 with 3000 segments still fits.
+ * All calls on one GPU share the one array, which keeps the tables of the last shape (a call
+ * with the same shape as the one before only launches the two kernels; another shape is uploaded
+ * in place): calls on the same GPU must not overlap, whatever their streams; the caller orders
+ * them (one stream, or events).  The caller still owns inputs and outputs.
+ */
+int dynamix_grad_aggregate_stats_static(const void* const* grads, const int32_t* batch_sizes,
+                                        int32_t K, int64_t P, int32_t dtype,
+                                        const int64_t* segment_offsets, int64_t num_segments,
+                                        float* out_agg, double* out_stats, void* stream);
 
 /*
  * The same pass with the model update fused in (Algorithm 1, the model-update half of its

@@ -16,6 +16,8 @@ DYNAMIX_F32, DYNAMIX_BF16, DYNAMIX_F16 = 0, 1, 2
 DYNAMIX_OK = 0
 DYNAMIX_ERR_NULL, DYNAMIX_ERR_ARG, DYNAMIX_ERR_SEGMENTS = 1, 2, 3
 DYNAMIX_ERR_ALIGN, DYNAMIX_ERR_NOMEM, DYNAMIX_ERR_HIP = 4, 5, 6
+DYNAMIX_ERR_CAPACITY = 7
+DYNAMIX_STATIC_SCRATCH_BYTES = 4 << 20
 DYNAMIX_K_MAX = 64
 DYNAMIX_STATS_HEAD = 8
 STAT = {"agg_sqnorm": 0, "tr_sigma": 1, "agg_sqnorm_unbiased": 2, "noise_scale": 3,
@@ -44,6 +46,8 @@ def load():
     lib.dynamix_grad_aggregate_stats.argtypes = [vp, vp, i32, i64, i32, vp, vp, vp, vp]
     lib.dynamix_grad_aggregate_stats_ex.restype = ctypes.c_int
     lib.dynamix_grad_aggregate_stats_ex.argtypes = [vp, vp, i32, i64, i32, vp, i64, vp, vp, vp]
+    lib.dynamix_grad_aggregate_stats_static.restype = ctypes.c_int
+    lib.dynamix_grad_aggregate_stats_static.argtypes = [vp, vp, i32, i64, i32, vp, i64, vp, vp, vp]
     lib.dynamix_grad_aggregate_stats_sgd.restype = ctypes.c_int
     lib.dynamix_grad_aggregate_stats_sgd.argtypes = [vp, vp, i32, i64, i32, vp, i64, vp,
                                                      ctypes.c_float, ctypes.c_float, vp, vp]
@@ -162,7 +166,7 @@ def dynamix_cycle_summary(window, K, num_segments, batch_sizes, eta, delta, summ
 
 
 def call_raw(grad_ptrs, batch_sizes, K, P, dtype, segment_offsets, num_segments, out_agg_ptr,
-             out_stats_ptr, stream_ptr, explicit_count=True):
+             out_stats_ptr, stream_ptr, explicit_count=True, static=False):
     """The C entry points on plain integers/sequences; returns the status.  grad_ptrs and
     batch_sizes may be None to pass NULL.  Used directly by the error-path tests."""
     lib = load()
@@ -171,6 +175,9 @@ def call_raw(grad_ptrs, batch_sizes, K, P, dtype, segment_offsets, num_segments,
     off = None
     if segment_offsets is not None:
         off = (ctypes.c_int64 * len(segment_offsets))(*segment_offsets)
+    if static:
+        return int(lib.dynamix_grad_aggregate_stats_static(
+            ptrs, b, K, P, dtype, off, num_segments, out_agg_ptr, out_stats_ptr, stream_ptr))
     if explicit_count:
         return int(lib.dynamix_grad_aggregate_stats_ex(
             ptrs, b, K, P, dtype, off, num_segments, out_agg_ptr, out_stats_ptr, stream_ptr))
@@ -222,6 +229,20 @@ def dynamix_grad_aggregate_stats_ex(grads, batch_sizes, segment_offsets=None, ou
     kw, out_agg, out_stats = _marshal(grads, batch_sizes, segment_offsets, out_agg, out_stats,
                                       stream, stats_only)
     rc = call_raw(explicit_count=True, **kw)
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+    return out_agg, out_stats
+
+
+def dynamix_grad_aggregate_stats_static(grads, batch_sizes, segment_offsets=None, out_agg=None,
+                                        out_stats=None, stream=None, stats_only=False):
+    """As dynamix_grad_aggregate_stats_ex, through the entry point whose workspace is the
+    library's static device array: the library allocates nothing (pass out_agg and out_stats, or
+    this wrapper allocates them with torch before the call).  Raises DynamixError with status
+    DYNAMIX_ERR_CAPACITY for a shape that needs more than DYNAMIX_STATIC_SCRATCH_BYTES."""
+    kw, out_agg, out_stats = _marshal(grads, batch_sizes, segment_offsets, out_agg, out_stats,
+                                      stream, stats_only)
+    rc = call_raw(static=True, **kw)
     if rc != DYNAMIX_OK:
         raise DynamixError(rc)
     return out_agg, out_stats

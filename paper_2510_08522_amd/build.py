@@ -123,15 +123,36 @@ def _compile(job):
     return "\n".join(lines)
 
 
+def _check_static_scratch():
+    """The static device array of the allocation-free entry point is looked up by name at run
+    time (hipGetSymbolAddress), and a lookup that fails aborts the process inside the runtime: the
+    array must be a global symbol of the device code (the compiler makes it one because host code
+    names it; with a `used` attribute on it, it does not)."""
+    src, asm = os.path.join(CSRC, "api.hip"), os.path.join(OBJ, "api_device.s")
+    r = subprocess.run([HIPCC] + FLAGS + ["--cuda-device-only", "-S", src, "-o", asm],
+                       stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc -S failed for api.hip:\n" + r.stdout)
+    with open(asm) as fh:
+        text = fh.read()
+    os.remove(asm)
+    if not re.search(r"^\s*\.globl\s+_ZL7scratch\s*$", text, re.MULTILINE):
+        raise RuntimeError("api.hip: the static scratch array is not a global device symbol")
+    if not re.search(r"\.globl\s+_ZL7scratch\s*\n\s*\.p2align\s+8\b", text):
+        raise RuntimeError("api.hip: the static scratch array is not 256-byte aligned")
+
+
 def build(verbose=False, workers=None):
     """Compile every unit and link the shared library; always recompiles."""
     os.makedirs(OBJ, exist_ok=True)
     jobs = _jobs()
     workers = workers or min(8, os.cpu_count() or 1)
     with ThreadPoolExecutor(max_workers=workers) as ex:
+        checked = ex.submit(_check_static_scratch)
         for out in ex.map(_compile, jobs):
             if verbose and out.strip():
                 print(out)
+        checked.result()
     cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + [j[1] for j in jobs]
     subprocess.run(cmd, check=True)
     return LIB

@@ -11,6 +11,13 @@
 #include "../../include/dynamix.h"
 #include "dynamix_internal.h"
 
+// Device memory of dynamix_grad_aggregate_stats_static, the entry point that allocates nothing:
+// plan tables, tail counter and partial sums of the call in flight.  Every GPU the library runs on
+// holds its own copy at its own address until the process ends; host code reaches it only through
+// the per-device address that hipGetSymbolAddress returns (static_scratch_of below), never
+// through this name.
+static __device__ __align__(256) unsigned char scratch[DYNAMIX_STATIC_SCRATCH_BYTES];
+
 namespace dynamix {
 
 #define DYNAMIX_UNIT_ENTRY(DT, LO) {launch_stream_pass_##DT##_##LO, occupancy_stream_pass_##DT##_##LO},
@@ -58,6 +65,9 @@ struct Plan {
     bool uploaded = false;
     std::vector<char> host;        // staging image of the tables
     size_t table_bytes = 0;
+    size_t total_bytes = 0;        // tables and partial sums
+    size_t o_block = 0, o_tail = 0, o_range = 0, o_count = 0, o_queue = 0, o_part = 0, o_slices = 0;
+    bool owns_blob = true;         // false: the blob is the library's static scratch array
     char* blob = nullptr;          // device: tables followed by the partial sums
     const Piece* d_pieces = nullptr;
     const int32_t* d_block_range = nullptr;
@@ -70,7 +80,7 @@ struct Plan {
     uint64_t last_use = 0;
     ~Plan()
     {
-        if (blob) (void)hipFree(blob);
+        if (blob && owns_blob) (void)hipFree(blob);
     }
 };
 
@@ -268,7 +278,9 @@ void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int
     }
 }
 
-int build_plan(Plan& pl, int S, const int64_t* offsets)
+// The tables of a plan and where each lies in the device blob (host arithmetic plus two device
+// queries; no device memory is touched).
+int layout_plan(Plan& pl, int S, const int64_t* offsets)
 {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, pl.device) != hipSuccess) return DYNAMIX_ERR_HIP;
@@ -286,41 +298,60 @@ int build_plan(Plan& pl, int S, const int64_t* offsets)
     pl.records = 1 + S;
 
     const int W = 2 * pl.K + 1;
-    const size_t o_pieces = 0;
-    const size_t o_block = align_up(o_pieces + L.pieces.size() * sizeof(Piece), 256);
-    const size_t o_tail = align_up(o_block + L.block_range.size() * sizeof(int32_t), 256);
-    const size_t o_range = align_up(o_tail + L.tail_order.size() * sizeof(int32_t), 256);
-    const size_t o_count = align_up(o_range + L.rec_range.size() * sizeof(int32_t), 256);
-    const size_t o_queue = align_up(o_count + L.rec_count.size() * sizeof(double), 256);
-    const size_t o_part = align_up(o_queue + sizeof(int32_t), 256);
+    pl.o_block = align_up(L.pieces.size() * sizeof(Piece), 256);
+    pl.o_tail = align_up(pl.o_block + L.block_range.size() * sizeof(int32_t), 256);
+    pl.o_range = align_up(pl.o_tail + L.tail_order.size() * sizeof(int32_t), 256);
+    pl.o_count = align_up(pl.o_range + L.rec_range.size() * sizeof(int32_t), 256);
+    pl.o_queue = align_up(pl.o_count + L.rec_count.size() * sizeof(double), 256);
+    pl.o_part = align_up(pl.o_queue + sizeof(int32_t), 256);
     // the final reduction shares record 0 among several blocks when it has many pieces
     pl.slices = pl.pieces >= kMinSlicedPieces ? std::min(kMaxSlices, pl.pieces / kPiecesPerSlice) : 1;
-    const size_t o_slices = align_up(o_part + (size_t)pl.pieces * W * sizeof(double), 256);
-    const size_t total = o_slices + (size_t)pl.slices * W * sizeof(double);
-    pl.table_bytes = o_part;
-    pl.host.assign(o_part, 0);
-    std::memcpy(pl.host.data() + o_pieces, L.pieces.data(), L.pieces.size() * sizeof(Piece));
-    std::memcpy(pl.host.data() + o_block, L.block_range.data(), L.block_range.size() * sizeof(int32_t));
+    pl.o_slices = align_up(pl.o_part + (size_t)pl.pieces * W * sizeof(double), 256);
+    pl.total_bytes = pl.o_slices + (size_t)pl.slices * W * sizeof(double);
+    pl.table_bytes = pl.o_part;
+    pl.host.assign(pl.o_part, 0);   // (the tail counter at o_queue starts at zero)
+    std::memcpy(pl.host.data(), L.pieces.data(), L.pieces.size() * sizeof(Piece));
+    std::memcpy(pl.host.data() + pl.o_block, L.block_range.data(), L.block_range.size() * sizeof(int32_t));
     if (!L.tail_order.empty())
-        std::memcpy(pl.host.data() + o_tail, L.tail_order.data(), L.tail_order.size() * sizeof(int32_t));
-    std::memcpy(pl.host.data() + o_range, L.rec_range.data(), L.rec_range.size() * sizeof(int32_t));
-    std::memcpy(pl.host.data() + o_count, L.rec_count.data(), L.rec_count.size() * sizeof(double));
+        std::memcpy(pl.host.data() + pl.o_tail, L.tail_order.data(), L.tail_order.size() * sizeof(int32_t));
+    std::memcpy(pl.host.data() + pl.o_range, L.rec_range.data(), L.rec_range.size() * sizeof(int32_t));
+    std::memcpy(pl.host.data() + pl.o_count, L.rec_count.data(), L.rec_count.size() * sizeof(double));
+    return DYNAMIX_OK;
+}
 
+// Points the plan at its device memory: total_bytes at `blob`.
+void bind_plan(Plan& pl, char* blob, bool owns)
+{
+    pl.blob = blob;
+    pl.owns_blob = owns;
+    pl.d_pieces = reinterpret_cast<const Piece*>(blob);
+    pl.d_block_range = reinterpret_cast<const int32_t*>(blob + pl.o_block);
+    pl.d_tail_order = reinterpret_cast<const int32_t*>(blob + pl.o_tail);
+    pl.d_rec_range = reinterpret_cast<const int32_t*>(blob + pl.o_range);
+    pl.d_rec_count = reinterpret_cast<const double*>(blob + pl.o_count);
+    pl.d_queue = reinterpret_cast<int32_t*>(blob + pl.o_queue);   // zero in the uploaded image
+    pl.d_partials = reinterpret_cast<double*>(blob + pl.o_part);
+    pl.d_slice_sums = reinterpret_cast<double*>(blob + pl.o_slices);
+}
+
+int build_plan(Plan& pl, int S, const int64_t* offsets)
+{
+    const int rc = layout_plan(pl, S, offsets);
+    if (rc != DYNAMIX_OK) return rc;
     void* dev = nullptr;
-    if (hipMalloc(&dev, total) != hipSuccess) {
+    if (hipMalloc(&dev, pl.total_bytes) != hipSuccess) {
         (void)hipGetLastError();
         return DYNAMIX_ERR_NOMEM;
     }
-    pl.blob = static_cast<char*>(dev);
-    pl.d_pieces = reinterpret_cast<const Piece*>(pl.blob + o_pieces);
-    pl.d_block_range = reinterpret_cast<const int32_t*>(pl.blob + o_block);
-    pl.d_tail_order = reinterpret_cast<const int32_t*>(pl.blob + o_tail);
-    pl.d_rec_range = reinterpret_cast<const int32_t*>(pl.blob + o_range);
-    pl.d_rec_count = reinterpret_cast<const double*>(pl.blob + o_count);
-    pl.d_partials = reinterpret_cast<double*>(pl.blob + o_part);
-    pl.d_queue = reinterpret_cast<int32_t*>(pl.blob + o_queue);   // zero in the uploaded image
-    pl.d_slice_sums = reinterpret_cast<double*>(pl.blob + o_slices);
+    bind_plan(pl, static_cast<char*>(dev), true);
     return DYNAMIX_OK;
+}
+
+bool same_shape(const Plan& pl, int K, int dtype, int64_t P, int S, const int64_t* offsets)
+{
+    return pl.K == K && pl.dtype == dtype && pl.P == P &&
+           (int)pl.offsets.size() == (S > 0 ? S + 1 : 0) &&
+           (S == 0 || std::memcmp(pl.offsets.data(), offsets, sizeof(int64_t) * (S + 1)) == 0);
 }
 
 // Finds or builds the plan; the caller holds g_mutex.
@@ -329,9 +360,7 @@ int get_plan(int device, hipStream_t stream, int K, int dtype, int64_t P, int S,
 {
     for (auto& up : g_plans) {
         Plan& pl = *up;
-        if (pl.device == device && pl.stream == stream && pl.K == K && pl.dtype == dtype &&
-            pl.P == P && (int)pl.offsets.size() == (S > 0 ? S + 1 : 0) &&
-            (S == 0 || std::memcmp(pl.offsets.data(), offsets, sizeof(int64_t) * (S + 1)) == 0)) {
+        if (pl.device == device && pl.stream == stream && same_shape(pl, K, dtype, P, S, offsets)) {
             pl.last_use = ++g_clock;
             *out = &pl;
             return DYNAMIX_OK;
@@ -358,6 +387,86 @@ int get_plan(int device, hipStream_t stream, int K, int dtype, int64_t P, int S,
     return DYNAMIX_OK;
 }
 
+// ---- the entry point that allocates nothing (for callers that cannot call hipMalloc)
+//
+// Its plan lives in the static scratch array instead of a hipMalloc'ed blob, one plan per device:
+// the tables of the last shape stay resident, another shape overwrites them.  The tables reach
+// the device in the arguments of a small kernel, 3.5 KB per launch on the caller's stream (an
+// asynchronous copy from pageable host memory would go through staging buffers that the runtime
+// allocates).
+constexpr int kPokeWords = 896;
+struct PokeArgs {
+    uint32_t words[kPokeWords];
+};
+__global__ __launch_bounds__(kPokeWords) void poke_kernel(uint32_t* dst, int n, const PokeArgs a)
+{
+    const int i = threadIdx.x;
+    if (i < n) dst[i] = a.words[i];
+}
+
+constexpr int kMaxDevices = 64;
+struct StaticDevice {
+    char* ptr = nullptr;            // this device's copy of the scratch array
+    std::unique_ptr<Plan> plan;     // the shape whose tables are resident (host side: layout only)
+};
+StaticDevice g_static[kMaxDevices];
+
+// The address of the current device's scratch array, looked up once per device.
+int static_scratch_of(int device, char** out)
+{
+    if (device < 0 || device >= kMaxDevices) return DYNAMIX_ERR_ARG;
+    StaticDevice& sd = g_static[device];
+    if (!sd.ptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return DYNAMIX_ERR_HIP;
+        }
+        sd.ptr = static_cast<char*>(p);
+    }
+    *out = sd.ptr;
+    return DYNAMIX_OK;
+}
+
+// Finds or lays out the plan of the static path; the caller holds g_mutex.
+int get_static_plan(int device, hipStream_t stream, int K, int dtype, int64_t P, int S,
+                    const int64_t* offsets, Plan** out)
+{
+    char* ptr = nullptr;
+    const int rc = static_scratch_of(device, &ptr);
+    if (rc != DYNAMIX_OK) return rc;
+    StaticDevice& sd = g_static[device];
+    if (!sd.plan || !same_shape(*sd.plan, K, dtype, P, S, offsets)) {
+        auto up = std::make_unique<Plan>();
+        up->device = device;
+        up->K = K;
+        up->dtype = dtype;
+        up->P = P;
+        if (S > 0) up->offsets.assign(offsets, offsets + S + 1);
+        const int lrc = layout_plan(*up, S, offsets);
+        if (lrc != DYNAMIX_OK) return lrc;
+        if (up->total_bytes > (size_t)DYNAMIX_STATIC_SCRATCH_BYTES) return DYNAMIX_ERR_CAPACITY;
+        bind_plan(*up, ptr, /*owns=*/false);
+        sd.plan = std::move(up);    // (the tables of the shape before are overwritten below)
+    }
+    sd.plan->stream = stream;
+    *out = sd.plan.get();
+    return DYNAMIX_OK;
+}
+
+// Writes the plan's tables (with a zero tail counter) into the scratch array, on `stream`.
+int upload_static(const Plan& pl, hipStream_t stream)
+{
+    PokeArgs pa;
+    for (size_t off = 0; off < pl.table_bytes; off += sizeof pa.words) {
+        const size_t nbytes = std::min(sizeof pa.words, pl.table_bytes - off);   // multiples of 256
+        std::memcpy(pa.words, pl.host.data() + off, nbytes);
+        poke_kernel<<<dim3(1), dim3(kPokeWords), 0, stream>>>(
+            reinterpret_cast<uint32_t*>(pl.blob + off), (int)(nbytes / 4), pa);
+    }
+    return hipGetLastError() == hipSuccess ? DYNAMIX_OK : DYNAMIX_ERR_HIP;
+}
+
 int check_shape(int32_t K, int64_t P, int32_t dtype, const int64_t* offsets, int64_t S)
 {
     if (K < 1 || K > kKMax || P < 1 || dtype < DYNAMIX_F32 || dtype > DYNAMIX_F16)
@@ -374,7 +483,7 @@ int check_shape(int32_t K, int64_t P, int32_t dtype, const int64_t* offsets, int
 
 int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t P, int32_t dtype,
         const int64_t* offsets, int64_t S, float* out_agg, double* out_stats, void* stream_v,
-        float* params = nullptr, float lr = 0.f, float weight_decay = 0.f)
+        float* params = nullptr, float lr = 0.f, float weight_decay = 0.f, bool use_static = false)
 {
     // ---- validation: no HIP call before this block has passed
     if (!grads || !batch_sizes || !out_stats) return DYNAMIX_ERR_NULL;
@@ -400,12 +509,16 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
 
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* pl = nullptr;
-    const int rc = get_plan(device, stream, K, dtype, P, (int)S, offsets, &pl);
+    const int rc = use_static ? get_static_plan(device, stream, K, dtype, P, (int)S, offsets, &pl)
+                              : get_plan(device, stream, K, dtype, P, (int)S, offsets, &pl);
     if (rc != DYNAMIX_OK) return rc;
     if (!pl->uploaded) {
-        if (hipMemcpyAsync(pl->blob, pl->host.data(), pl->table_bytes, hipMemcpyHostToDevice,
-                           stream) != hipSuccess)
+        if (use_static) {
+            if (upload_static(*pl, stream) != DYNAMIX_OK) return DYNAMIX_ERR_HIP;
+        } else if (hipMemcpyAsync(pl->blob, pl->host.data(), pl->table_bytes,
+                                  hipMemcpyHostToDevice, stream) != hipSuccess) {
             return DYNAMIX_ERR_HIP;
+        }
         pl->uploaded = true;
     }
 
@@ -479,6 +592,21 @@ int dynamix_grad_aggregate_stats_ex(const void* const* grads, const int32_t* bat
     }
 }
 
+int dynamix_grad_aggregate_stats_static(const void* const* grads, const int32_t* batch_sizes,
+                                        int32_t K, int64_t P, int32_t dtype,
+                                        const int64_t* segment_offsets, int64_t num_segments,
+                                        float* out_agg, double* out_stats, void* stream)
+{
+    try {
+        return dynamix::run(grads, batch_sizes, K, P, dtype, segment_offsets, num_segments, out_agg,
+                            out_stats, stream, nullptr, 0.f, 0.f, /*use_static=*/true);
+    } catch (const std::bad_alloc&) {
+        return DYNAMIX_ERR_NOMEM;
+    } catch (...) {
+        return DYNAMIX_ERR_HIP;
+    }
+}
+
 int dynamix_grad_aggregate_stats_sgd(const void* const* grads, const int32_t* batch_sizes,
                                      int32_t K, int64_t P, int32_t dtype,
                                      const int64_t* segment_offsets, int64_t num_segments,
@@ -532,6 +660,7 @@ const char* dynamix_status_string(int status)
     case DYNAMIX_ERR_ALIGN: return "misaligned pointer";
     case DYNAMIX_ERR_NOMEM: return "workspace allocation failed";
     case DYNAMIX_ERR_HIP: return "HIP runtime call failed";
+    case DYNAMIX_ERR_CAPACITY: return "shape exceeds the static scratch buffer";
     default: return "unknown status";
     }
 }
@@ -606,6 +735,7 @@ int dynamix_release_cached(void)
 {
     std::lock_guard<std::mutex> lock(dynamix::g_mutex);
     dynamix::g_plans.clear();
+    for (auto& sd : dynamix::g_static) sd.plan.reset();   // host side only: the array itself stays
     return DYNAMIX_OK;
 }
 

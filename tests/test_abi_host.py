@@ -63,8 +63,8 @@ def test_stats_count_and_status_strings():
     assert D.dynamix_stats_count(32, 148) == 149 * 72
     assert D.dynamix_stats_count(0, 0) == -1 and D.dynamix_stats_count(65, 0) == -1
     assert D.dynamix_stats_count(4, -1) == -1
-    seen = {D.dynamix_status_string(i) for i in range(7)}
-    assert len(seen) == 7 and D.dynamix_status_string(0) == "ok"
+    seen = {D.dynamix_status_string(i) for i in range(8)}
+    assert len(seen) == 8 and D.dynamix_status_string(0) == "ok"
     assert D.dynamix_status_string(99) == "unknown status"
 
 
