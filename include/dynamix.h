@@ -226,6 +226,25 @@ int32_t dynamix_timing_count(void);
 int     dynamix_timing_read(int32_t index, float* stream_pass_ms, float* final_reduce_ms);
 
 /*
+ * Measurement aid, not part of the path: plain streaming kernels in the launch shape and access
+ * pattern of the streaming pass (one block of 256 threads per compute unit, contiguous span per
+ * block, 128-bit non-temporal buffer accesses) with no arithmetic, to measure what the memory
+ * system gives such a kernel.  `buffers`: HOST array of `count` DEVICE pointers, 256-byte aligned,
+ * `bytes` each (a multiple of 4096 is used).  Modes:
+ *   DYNAMIX_PROBE_READ         read `count` (1, 2, 4, 8, 16 or 32) buffers, 4 KB tiles in order
+ *   DYNAMIX_PROBE_READ_SPREAD  the same in the interleaved 256-byte chunks of the streaming pass
+ *   DYNAMIX_PROBE_WRITE        count == 1: write buffers[0]
+ *   DYNAMIX_PROBE_COPY         count == 2: buffers[1] := buffers[0]
+ * Every probe kernel reserves more than half of a compute unit's LDS, so two probes launched
+ * together on two streams with n and (compute units - n) blocks run on disjoint units: that is
+ * how reading beside writing is measured.  Only enqueues one kernel on `stream`; validates first.
+ */
+enum { DYNAMIX_PROBE_READ = 0, DYNAMIX_PROBE_READ_SPREAD = 1, DYNAMIX_PROBE_WRITE = 2,
+       DYNAMIX_PROBE_COPY = 3 };
+int dynamix_hbm_probe(const void* const* buffers, int32_t count, int64_t bytes, int32_t mode,
+                      int32_t blocks, void* stream);
+
+/*
  * Environment: DYNAMIX_MAX_BLOCKS=n (n >= 1) caps the number of blocks the streaming pass is
  * launched with; it is read whenever a plan is built (first call for a shape).  A tuning and
  * testing aid: results do not depend on it beyond the order of the fp64 partial sums.

@@ -70,6 +70,8 @@ def load():
     lib.dynamix_cycle_summary.argtypes = [vp, i32, i64, vp, ctypes.c_double, ctypes.c_double, vp, vp]
     lib.dynamix_cycle_summary_count.restype = i64
     lib.dynamix_cycle_summary_count.argtypes = [i32, i64]
+    lib.dynamix_hbm_probe.restype = ctypes.c_int
+    lib.dynamix_hbm_probe.argtypes = [vp, i32, i64, i32, i32, vp]
     lib.dynamix_release_cached.restype = ctypes.c_int
     lib.dynamix_release_cached.argtypes = []
     _lib = lib
@@ -86,6 +88,22 @@ def dynamix_status_string(status):
 
 def dynamix_release_cached():
     return int(load().dynamix_release_cached())
+
+
+DYNAMIX_PROBE_READ, DYNAMIX_PROBE_READ_SPREAD, DYNAMIX_PROBE_WRITE, DYNAMIX_PROBE_COPY = 0, 1, 2, 3
+
+
+def dynamix_hbm_probe(buffers, nbytes, mode, blocks, stream=None):
+    """Enqueue one of the plain streaming kernels (measurement aid) over `buffers`, device tensors
+    of at least `nbytes` bytes each."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(buffers[0].device)
+    ptrs = (ctypes.c_void_p * len(buffers))(*[t.data_ptr() for t in buffers])
+    rc = int(load().dynamix_hbm_probe(ptrs, len(buffers), int(nbytes), int(mode), int(blocks),
+                                      stream.cuda_stream))
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
 
 
 def dynamix_plan_describe(K, P, dtype, segment_offsets=None, max_blocks=256):

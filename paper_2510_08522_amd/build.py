@@ -30,6 +30,7 @@ def _jobs():
                          ["-DDYNAMIX_INST_DT=%d" % dt, "-DDYNAMIX_INST_LO=%d" % lo]))
     jobs.append((os.path.join(CSRC, "final_reduce.hip"), os.path.join(OBJ, "final_reduce.o"), []))
     jobs.append((os.path.join(CSRC, "cycle.hip"), os.path.join(OBJ, "cycle.o"), []))
+    jobs.append((os.path.join(CSRC, "hbm_probe.hip"), os.path.join(OBJ, "hbm_probe.o"), []))
     jobs.append((os.path.join(CSRC, "api.hip"), os.path.join(OBJ, "api.o"), []))
     return jobs
 
