@@ -6,9 +6,11 @@ It shares no code with the HIP path and never imports it.
 from .dynamix_oracle import (  # noqa: F401
     HEAD,
     IDX,
+    adam_step,
     aggregate_stats,
     build,
     max_threads,
+    sgd_momentum_step,
     sgd_step,
     stats_count,
     widen,

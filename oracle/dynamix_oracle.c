@@ -220,6 +220,69 @@ int dynamix_oracle_sgd_step(const double *agg, const float *params, int64_t P, d
     return 0;
 }
 
+/*
+ * SGD with momentum on the aggregate (the paper trains with SGD, Evaluation, experimental setup,
+ * and prints no update rule; this is the textbook heavy-ball form that the common frameworks use,
+ * zero dampening):
+ *     g'   = G_i + wd * p_i
+ *     buf' = mu * buf_i + g'
+ *     step = g' + mu * buf'   (Nesterov)   or   buf'   (plain)
+ *     p'   = p_i - lr * step
+ * A momentum buffer of zeros makes the first step equal to plain SGD.  params, buf: P floats
+ * (widened exactly); agg: P doubles; out_params, out_buf: P doubles.  Long double throughout.
+ */
+int dynamix_oracle_sgd_momentum_step(const double *agg, const float *params, const float *buf,
+                                     int64_t P, double lr, double weight_decay, double momentum,
+                                     int32_t nesterov, double *out_params, double *out_buf)
+{
+    if (!agg || !params || !buf || !out_params || !out_buf || P < 1)
+        return 1;
+    for (int64_t i = 0; i < P; ++i) {
+        acc_t p = (acc_t)params[i];
+        acc_t g = (acc_t)agg[i] + (acc_t)weight_decay * p;
+        acc_t b = (acc_t)momentum * (acc_t)buf[i] + g;
+        acc_t step = nesterov ? g + (acc_t)momentum * b : b;
+        out_buf[i] = (double)b;
+        out_params[i] = (double)(p - (acc_t)lr * step);
+    }
+    return 0;
+}
+
+/*
+ * Adam on the aggregate (the paper's second optimizer; its sigma_norm statistics are motivated by
+ * the normalisation Adam applies; no update rule is printed, this is the published algorithm of
+ * Kingma and Ba with bias correction, t = step >= 1):
+ *     g'  = G_i + wd * p_i                       (L2 form; decoupled: g' = G_i, p_i <- p_i (1 - lr wd))
+ *     m'  = beta1 * m_i + (1 - beta1) * g'
+ *     v'  = beta2 * v_i + (1 - beta2) * g'^2
+ *     p'  = p_i - lr * (m' / (1 - beta1^t)) / (sqrt(v' / (1 - beta2^t)) + eps)
+ * params, m, v: P floats (widened exactly); agg: P doubles; outputs: P doubles each.
+ */
+int dynamix_oracle_adam_step(const double *agg, const float *params, const float *m, const float *v,
+                             int64_t P, double lr, double beta1, double beta2, double eps,
+                             double weight_decay, int32_t decoupled, int64_t step,
+                             double *out_params, double *out_m, double *out_v)
+{
+    if (!agg || !params || !m || !v || !out_params || !out_m || !out_v || P < 1 || step < 1)
+        return 1;
+    acc_t c1 = 1 - powl((acc_t)beta1, (acc_t)step);
+    acc_t c2 = 1 - powl((acc_t)beta2, (acc_t)step);
+    for (int64_t i = 0; i < P; ++i) {
+        acc_t p = (acc_t)params[i];
+        acc_t g = (acc_t)agg[i];
+        if (decoupled)
+            p = p * (1 - (acc_t)lr * (acc_t)weight_decay);
+        else
+            g = g + (acc_t)weight_decay * p;
+        acc_t mn = (acc_t)beta1 * (acc_t)m[i] + (1 - (acc_t)beta1) * g;
+        acc_t vn = (acc_t)beta2 * (acc_t)v[i] + (1 - (acc_t)beta2) * g * g;
+        out_m[i] = (double)mn;
+        out_v[i] = (double)vn;
+        out_params[i] = (double)(p - (acc_t)lr * (mn / c1) / (sqrtl(vn / c2) + (acc_t)eps));
+    }
+    return 0;
+}
+
 int dynamix_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -52,6 +52,15 @@ def _load():
         lib.dynamix_oracle_sgd_step.argtypes = [
             ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_float), ctypes.c_int64,
             ctypes.c_double, ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
+        dp, fp = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_float)
+        lib.dynamix_oracle_sgd_momentum_step.restype = ctypes.c_int
+        lib.dynamix_oracle_sgd_momentum_step.argtypes = [
+            dp, fp, fp, ctypes.c_int64, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+            ctypes.c_int32, dp, dp]
+        lib.dynamix_oracle_adam_step.restype = ctypes.c_int
+        lib.dynamix_oracle_adam_step.argtypes = [
+            dp, fp, fp, fp, ctypes.c_int64, ctypes.c_double, ctypes.c_double, ctypes.c_double,
+            ctypes.c_double, ctypes.c_double, ctypes.c_int32, ctypes.c_int64, dp, dp, dp]
         lib.dynamix_oracle_max_threads.restype = ctypes.c_int
         lib.dynamix_oracle_widen.restype = ctypes.c_int
         lib.dynamix_oracle_widen.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64,
@@ -142,3 +151,54 @@ def sgd_step(agg, params, lr, weight_decay=0.0):
     if rc != 0:
         raise ValueError("oracle rejected its arguments")
     return out
+
+
+def _f32(a, shape):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.float32 or a.shape != shape:
+        raise TypeError("parameters and optimizer state must be float32 and match agg")
+    return a
+
+
+def _dp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _fp(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def sgd_momentum_step(agg, params, buf, lr, weight_decay=0.0, momentum=0.0, nesterov=False):
+    """One step of SGD with momentum on G = agg (float64[P]); params and buf float32[P].
+    Returns (new params, new momentum buffer) as float64[P]."""
+    lib = _load()
+    agg = np.ascontiguousarray(agg, dtype=np.float64)
+    if agg.ndim != 1:
+        raise TypeError("agg must be 1-d")
+    params, buf = _f32(params, agg.shape), _f32(buf, agg.shape)
+    out_p, out_b = np.empty_like(agg), np.empty_like(agg)
+    rc = lib.dynamix_oracle_sgd_momentum_step(_dp(agg), _fp(params), _fp(buf), agg.shape[0],
+                                              float(lr), float(weight_decay), float(momentum),
+                                              int(bool(nesterov)), _dp(out_p), _dp(out_b))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return out_p, out_b
+
+
+def adam_step(agg, params, exp_avg, exp_avg_sq, lr, beta1=0.9, beta2=0.999, eps=1e-8,
+              weight_decay=0.0, decoupled=False, step=1):
+    """One step of Adam (decoupled: AdamW) on G = agg (float64[P]); params and the two moment
+    estimates float32[P]; step counts from 1.  Returns (params, exp_avg, exp_avg_sq) as float64[P]."""
+    lib = _load()
+    agg = np.ascontiguousarray(agg, dtype=np.float64)
+    if agg.ndim != 1:
+        raise TypeError("agg must be 1-d")
+    params, m, v = (_f32(x, agg.shape) for x in (params, exp_avg, exp_avg_sq))
+    out_p, out_m, out_v = np.empty_like(agg), np.empty_like(agg), np.empty_like(agg)
+    rc = lib.dynamix_oracle_adam_step(_dp(agg), _fp(params), _fp(m), _fp(v), agg.shape[0],
+                                      float(lr), float(beta1), float(beta2), float(eps),
+                                      float(weight_decay), int(bool(decoupled)), int(step),
+                                      _dp(out_p), _dp(out_m), _dp(out_v))
+    if rc != 0:
+        raise ValueError("oracle rejected its arguments")
+    return out_p, out_m, out_v
