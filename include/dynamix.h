@@ -53,6 +53,7 @@ typedef enum {
 } dynamix_status;
 
 enum { DYNAMIX_K_MAX = 64 };        /* most workers per call: pointers and weights travel in the kernel arguments */
+enum { DYNAMIX_K_MAX_STATEFUL = 24 }; /* most workers for the fused updates that carry optimizer state */
 enum { DYNAMIX_STATIC_SCRATCH_BYTES = 4 << 20 }; /* workspace of dynamix_grad_aggregate_stats_static */
 enum { DYNAMIX_STATS_HEAD = 8 };    /* scalars in front of the per-worker entries of a record */
 
@@ -156,6 +157,45 @@ int dynamix_grad_aggregate_stats_sgd(const void* const* grads, const int32_t* ba
                                      const int64_t* segment_offsets, int64_t num_segments,
                                      float* params, float lr, float weight_decay,
                                      double* out_stats, void* stream);
+
+/*
+ * The pass with a model update that carries optimizer state fused in (Algorithm 1, the
+ * model-update half of its gradient step; the paper trains with SGD and with Adam, "Evaluation",
+ * experimental setup, and prints no update rule: the rules below are the published ones the common
+ * frameworks implement).  The state vectors travel through the pass as further streams, read and
+ * rewritten in place like params, so neither G nor the state makes an extra round trip through
+ * HBM.  params and every state vector: DEVICE, P floats, 16-byte aligned, not overlapping each
+ * other or any gradient buffer.  K <= DYNAMIX_K_MAX_STATEFUL (above, the K gradient vectors of a
+ * lane and the state leave no registers; DYNAMIX_ERR_ARG).  Statistics, segments, stream,
+ * validation and error behaviour as for dynamix_grad_aggregate_stats_ex; the statistics are those
+ * of the gradients (these kernels take fewer vectors per block iteration, so the partial sums are
+ * added in another order than in the plain call).  All arithmetic of the updates is fp32 (fused multiply-adds,
+ * IEEE division and square root), constants that depend only on the scalars are formed once on the
+ * host in double.
+ *
+ * dynamix_grad_aggregate_stats_sgd_momentum -- heavy-ball momentum, zero dampening:
+ *     g = G_i + weight_decay p_i;   buf_i <- momentum buf_i + g;
+ *     p_i <- p_i - lr (nesterov ? g + momentum buf_i : buf_i)
+ * A zero momentum_buf makes the first step plain SGD.
+ *
+ * dynamix_grad_aggregate_stats_adam -- Adam with bias correction, step = t >= 1 (the caller
+ * counts); 0 <= beta < 1:
+ *     g = G_i + weight_decay p_i            (decoupled != 0: g = G_i and p_i <- p_i (1 - lr weight_decay) first)
+ *     m_i <- beta1 m_i + (1 - beta1) g;     v_i <- beta2 v_i + (1 - beta2) g^2
+ *     p_i <- p_i - lr (m_i / (1 - beta1^t)) / (sqrt(v_i / (1 - beta2^t)) + eps)
+ */
+int dynamix_grad_aggregate_stats_sgd_momentum(const void* const* grads, const int32_t* batch_sizes,
+                                              int32_t K, int64_t P, int32_t dtype,
+                                              const int64_t* segment_offsets, int64_t num_segments,
+                                              float* params, float* momentum_buf, float lr,
+                                              float weight_decay, float momentum, int32_t nesterov,
+                                              double* out_stats, void* stream);
+int dynamix_grad_aggregate_stats_adam(const void* const* grads, const int32_t* batch_sizes, int32_t K,
+                                      int64_t P, int32_t dtype, const int64_t* segment_offsets,
+                                      int64_t num_segments, float* params, float* exp_avg,
+                                      float* exp_avg_sq, float lr, float beta1, float beta2, float eps,
+                                      float weight_decay, int32_t decoupled, int64_t step,
+                                      double* out_stats, void* stream);
 
 /* Doubles needed for out_stats: (1 + S) * (DYNAMIX_STATS_HEAD + 2K); S = 0 without segments.
  * Returns -1 for K outside 1..DYNAMIX_K_MAX or S < 0. */

@@ -19,6 +19,7 @@ DYNAMIX_ERR_ALIGN, DYNAMIX_ERR_NOMEM, DYNAMIX_ERR_HIP = 4, 5, 6
 DYNAMIX_ERR_CAPACITY = 7
 DYNAMIX_STATIC_SCRATCH_BYTES = 4 << 20
 DYNAMIX_K_MAX = 64
+DYNAMIX_K_MAX_STATEFUL = 24
 DYNAMIX_STATS_HEAD = 8
 STAT = {"agg_sqnorm": 0, "tr_sigma": 1, "agg_sqnorm_unbiased": 2, "noise_scale": 3,
         "noise_scale_biased": 4, "sigma2_norm": 5, "sigma_norm": 6, "count": 7}
@@ -51,6 +52,13 @@ def load():
     lib.dynamix_grad_aggregate_stats_sgd.restype = ctypes.c_int
     lib.dynamix_grad_aggregate_stats_sgd.argtypes = [vp, vp, i32, i64, i32, vp, i64, vp,
                                                      ctypes.c_float, ctypes.c_float, vp, vp]
+    f32 = ctypes.c_float
+    lib.dynamix_grad_aggregate_stats_sgd_momentum.restype = ctypes.c_int
+    lib.dynamix_grad_aggregate_stats_sgd_momentum.argtypes = [vp, vp, i32, i64, i32, vp, i64, vp, vp,
+                                                              f32, f32, f32, i32, vp, vp]
+    lib.dynamix_grad_aggregate_stats_adam.restype = ctypes.c_int
+    lib.dynamix_grad_aggregate_stats_adam.argtypes = [vp, vp, i32, i64, i32, vp, i64, vp, vp, vp,
+                                                      f32, f32, f32, f32, f32, i32, i64, vp, vp]
     lib.dynamix_stats_count.restype = i64
     lib.dynamix_stats_count.argtypes = [i32, i64]
     lib.dynamix_status_string.restype = ctypes.c_char_p
@@ -297,6 +305,59 @@ def dynamix_grad_aggregate_stats_sgd(grads, batch_sizes, params, lr, weight_deca
     rc = int(lib.dynamix_grad_aggregate_stats_sgd(
         ptrs, b, K, kw["P"], kw["dtype"], off, kw["num_segments"], params.data_ptr(), float(lr),
         float(weight_decay), kw["out_stats_ptr"], kw["stream_ptr"]))
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+    return out_stats
+
+
+def _update_args(grads, batch_sizes, segment_offsets, out_stats, stream, tensors):
+    """C arguments shared by the fused-update entry points; `tensors` are the parameter and state
+    tensors, checked here."""
+    import torch
+    for t in tensors:
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == torch.float32
+                and t.numel() == grads[0].numel()):
+            raise ValueError("parameters and optimizer state must be contiguous float32 device "
+                             "tensors of P elements")
+    kw, _, out_stats = _marshal(grads, batch_sizes, segment_offsets, None, out_stats, stream, True)
+    K = kw["K"]
+    ptrs = (ctypes.c_void_p * K)(*kw["grad_ptrs"])
+    b = (ctypes.c_int32 * K)(*kw["batch_sizes"])
+    off = None
+    if kw["segment_offsets"] is not None:
+        off = (ctypes.c_int64 * len(kw["segment_offsets"]))(*kw["segment_offsets"])
+    head = (ptrs, b, K, kw["P"], kw["dtype"], off, kw["num_segments"])
+    return head, kw["out_stats_ptr"], kw["stream_ptr"], out_stats
+
+
+def dynamix_grad_aggregate_stats_sgd_momentum(grads, batch_sizes, params, momentum_buf, lr,
+                                              weight_decay=0.0, momentum=0.9, nesterov=False,
+                                              segment_offsets=None, out_stats=None, stream=None):
+    """Aggregate + statistics with SGD with momentum fused in: params and momentum_buf
+    (float32[P] device tensors) are updated in place.  Returns out_stats."""
+    head, st_ptr, s_ptr, out_stats = _update_args(grads, batch_sizes, segment_offsets, out_stats,
+                                                  stream, (params, momentum_buf))
+    rc = int(load().dynamix_grad_aggregate_stats_sgd_momentum(
+        *head, params.data_ptr(), momentum_buf.data_ptr(), float(lr), float(weight_decay),
+        float(momentum), int(bool(nesterov)), st_ptr, s_ptr))
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+    return out_stats
+
+
+def dynamix_grad_aggregate_stats_adam(grads, batch_sizes, params, exp_avg, exp_avg_sq, lr, step,
+                                      beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
+                                      decoupled=False, segment_offsets=None, out_stats=None,
+                                      stream=None):
+    """Aggregate + statistics with an Adam step (decoupled: AdamW) fused in: params, exp_avg and
+    exp_avg_sq (float32[P] device tensors) are updated in place; step counts from 1.  Returns
+    out_stats."""
+    head, st_ptr, s_ptr, out_stats = _update_args(grads, batch_sizes, segment_offsets, out_stats,
+                                                  stream, (params, exp_avg, exp_avg_sq))
+    rc = int(load().dynamix_grad_aggregate_stats_adam(
+        *head, params.data_ptr(), exp_avg.data_ptr(), exp_avg_sq.data_ptr(), float(lr),
+        float(beta1), float(beta2), float(eps), float(weight_decay), int(bool(decoupled)),
+        int(step), st_ptr, s_ptr))
     if rc != DYNAMIX_OK:
         raise DynamixError(rc)
     return out_stats

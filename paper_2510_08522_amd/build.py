@@ -1,7 +1,8 @@
 """Builds libdynamix.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
 
-The streaming pass is instantiated for every K in 1..64 and the three storage types; the
-instantiations are split over 24 translation units that compile in parallel.
+The streaming pass is instantiated for every K in 1..64 and the three storage types, and again
+for K in 1..24 with each of the two optimizer updates that carry state; the instantiations are
+split over 42 translation units of eight kernels that compile in parallel.
 Run as `python -m paper_2510_08522_amd.build`.
 """
 import os
@@ -23,11 +24,13 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-u
 
 def _jobs():
     jobs = []
-    for dt in (0, 1, 2):
-        for lo in range(1, 65, 8):
-            jobs.append((os.path.join(CSRC, "stream_pass_inst.hip"),
-                         os.path.join(OBJ, "stream_pass_%d_%d.o" % (dt, lo)),
-                         ["-DDYNAMIX_INST_DT=%d" % dt, "-DDYNAMIX_INST_LO=%d" % lo]))
+    for opt in (0, 1, 2):
+        for dt in (0, 1, 2):
+            for lo in range(1, 65 if opt == 0 else 25, 8):
+                jobs.append((os.path.join(CSRC, "stream_pass_inst.hip"),
+                             os.path.join(OBJ, "stream_pass_%d_%d_%d.o" % (opt, dt, lo)),
+                             ["-DDYNAMIX_INST_OPT=%d" % opt, "-DDYNAMIX_INST_DT=%d" % dt,
+                              "-DDYNAMIX_INST_LO=%d" % lo]))
     jobs.append((os.path.join(CSRC, "final_reduce.hip"), os.path.join(OBJ, "final_reduce.o"), []))
     jobs.append((os.path.join(CSRC, "cycle.hip"), os.path.join(OBJ, "cycle.o"), []))
     jobs.append((os.path.join(CSRC, "hbm_probe.hip"), os.path.join(OBJ, "hbm_probe.o"), []))
@@ -35,10 +38,10 @@ def _jobs():
     return jobs
 
 
-_KERNEL = re.compile(r"stream_pass_kernelILi(\d+)ELi(\d+)ELi(\d+)E")
+_KERNEL = re.compile(r"stream_pass_kernelILi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)E")
 
 
-def _bank_registers(K, dtype, U):
+def _bank_registers(K, dtype, U, opt=0):
     """Accumulation registers the streaming pass uses on purpose (its two register banks): the
     same arithmetic as Shape<> in csrc/stream_pass.h."""
     if K > 44:
@@ -46,8 +49,9 @@ def _bank_registers(K, dtype, U):
     LW, kBlock, stage = (4 if K <= 32 else 2), 256, 152 * 1024
     Q = (1 if dtype == 0 else 2)
     slots = stage // (kBlock * LW * 4)
-    per_tile = U * Q * LW
-    first = (slots // (U * Q)) * per_tile
+    per_tile_slots = U * Q * (1 + opt)          # a parked tile holds one vector per output stream
+    per_tile = per_tile_slots * LW
+    first = (slots // per_tile_slots) * per_tile
     second = (256 - first) // per_tile * per_tile
     return first + second
 
@@ -71,16 +75,16 @@ def _check_resources(remarks, src):
                 continue
             what, value = m.group(1), int(m.group(2))
             if what == "AGPRs" and value != _bank_registers(*name):
-                bad.append("K=%d dtype=%d: %d accumulation registers, expected %d"
-                           % (name[0], name[1], value, _bank_registers(*name)))
+                bad.append("K=%d dtype=%d opt=%d: %d accumulation registers, expected %d"
+                           % (name[0], name[1], name[3], value, _bank_registers(*name)))
             elif what.startswith("Scratch") and value != 0:
                 scratch[name] = value
             elif what == "VGPRs Spill" and value != 0:
-                bad.append("K=%d dtype=%d: %d vector registers spilled" % (name[0], name[1], value))
+                bad.append("K=%d dtype=%d opt=%d: %d vector registers spilled" % (name[0], name[1], name[3], value))
     spilled = {b.split(":")[0] for b in bad if "spilled" in b}
     for name, value in scratch.items():
-        if "K=%d dtype=%d" % name[:2] in spilled:
-            bad.append("K=%d dtype=%d: %d bytes of scratch" % (name[0], name[1], value))
+        if "K=%d dtype=%d opt=%d" % (name[0], name[1], name[3]) in spilled:
+            bad.append("K=%d dtype=%d opt=%d: %d bytes of scratch" % (name[0], name[1], name[3], value))
         else:
             reserved.append(name)
     if bad:

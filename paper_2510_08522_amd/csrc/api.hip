@@ -20,32 +20,42 @@ static __device__ __align__(256) unsigned char scratch[DYNAMIX_STATIC_SCRATCH_BY
 
 namespace dynamix {
 
-#define DYNAMIX_UNIT_ENTRY(DT, LO) {launch_stream_pass_##DT##_##LO, occupancy_stream_pass_##DT##_##LO},
+#define DYNAMIX_UNIT_ENTRY(OPT, DT, LO) \
+    {launch_stream_pass_##OPT##_##DT##_##LO, occupancy_stream_pass_##OPT##_##DT##_##LO},
 struct Unit {
     hipError_t (*launch)(int, int, const StreamArgs&, hipStream_t);
     int (*occupancy)(int);
 };
-static const Unit kUnits[kDtypes][kKMax / 8] = {
-    {DYNAMIX_UNIT_ENTRY(0, 1) DYNAMIX_UNIT_ENTRY(0, 9) DYNAMIX_UNIT_ENTRY(0, 17)
-         DYNAMIX_UNIT_ENTRY(0, 25) DYNAMIX_UNIT_ENTRY(0, 33) DYNAMIX_UNIT_ENTRY(0, 41)
-             DYNAMIX_UNIT_ENTRY(0, 49) DYNAMIX_UNIT_ENTRY(0, 57)},
-    {DYNAMIX_UNIT_ENTRY(1, 1) DYNAMIX_UNIT_ENTRY(1, 9) DYNAMIX_UNIT_ENTRY(1, 17)
-         DYNAMIX_UNIT_ENTRY(1, 25) DYNAMIX_UNIT_ENTRY(1, 33) DYNAMIX_UNIT_ENTRY(1, 41)
-             DYNAMIX_UNIT_ENTRY(1, 49) DYNAMIX_UNIT_ENTRY(1, 57)},
-    {DYNAMIX_UNIT_ENTRY(2, 1) DYNAMIX_UNIT_ENTRY(2, 9) DYNAMIX_UNIT_ENTRY(2, 17)
-         DYNAMIX_UNIT_ENTRY(2, 25) DYNAMIX_UNIT_ENTRY(2, 33) DYNAMIX_UNIT_ENTRY(2, 41)
-             DYNAMIX_UNIT_ENTRY(2, 49) DYNAMIX_UNIT_ENTRY(2, 57)}};
+// [update kind][dtype][(K - 1) / 8]; the updates with state exist up to kKMaxOpt workers
+static const Unit kUnits[kOpts][kDtypes][kKMax / 8] = {
+    {{DYNAMIX_FOR_EACH_PLAIN_UNIT(DYNAMIX_UNIT_ENTRY, 0)},
+     {DYNAMIX_FOR_EACH_PLAIN_UNIT(DYNAMIX_UNIT_ENTRY, 1)},
+     {DYNAMIX_FOR_EACH_PLAIN_UNIT(DYNAMIX_UNIT_ENTRY, 2)}},
+    {{DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_UNIT_ENTRY, 1, 0)},
+     {DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_UNIT_ENTRY, 1, 1)},
+     {DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_UNIT_ENTRY, 1, 2)}},
+    {{DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_UNIT_ENTRY, 2, 0)},
+     {DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_UNIT_ENTRY, 2, 1)},
+     {DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_UNIT_ENTRY, 2, 2)}}};
 
-hipError_t launch_stream_pass(int K, int dtype, int grid, const StreamArgs& a, hipStream_t s)
+static const Unit* unit_for(int K, int dtype, int opt)
 {
-    if (K < 1 || K > kKMax || dtype < 0 || dtype >= kDtypes) return hipErrorInvalidValue;
-    return kUnits[dtype][(K - 1) / 8].launch(K, grid, a, s);
+    if (K < 1 || K > kKMax || dtype < 0 || dtype >= kDtypes || opt < 0 || opt >= kOpts) return nullptr;
+    if (opt != kOptNone && K > kKMaxOpt) return nullptr;
+    const Unit* u = &kUnits[opt][dtype][(K - 1) / 8];
+    return u->launch ? u : nullptr;
 }
 
-int stream_pass_blocks_per_cu(int K, int dtype)
+hipError_t launch_stream_pass(int K, int dtype, int opt, int grid, const StreamArgs& a, hipStream_t s)
 {
-    if (K < 1 || K > kKMax || dtype < 0 || dtype >= kDtypes) return 0;
-    return kUnits[dtype][(K - 1) / 8].occupancy(K);
+    const Unit* u = unit_for(K, dtype, opt);
+    return u ? u->launch(K, grid, a, s) : hipErrorInvalidValue;
+}
+
+int stream_pass_blocks_per_cu(int K, int dtype, int opt)
+{
+    const Unit* u = unit_for(K, dtype, opt);
+    return u ? u->occupancy(K) : 0;
 }
 
 namespace {
@@ -58,7 +68,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct Plan {
     int device = 0;
     hipStream_t stream = nullptr;
-    int K = 0, dtype = 0;
+    int K = 0, dtype = 0, opt = 0;
     int64_t P = 0;
     std::vector<int64_t> offsets;  // empty without segments
     int grid = 0, pieces = 0, n_tail = 0, records = 0, slices = 1;
@@ -130,11 +140,11 @@ struct Layout {
     std::vector<double> rec_count;
 };
 
-void make_layout(int K, int dtype, int64_t P, int S, const int64_t* offsets, int64_t max_grid,
+void make_layout(int K, int dtype, int opt, int64_t P, int S, const int64_t* offsets, int64_t max_grid,
                  Layout& L)
 {
     const int VEC = vec_elems(K, dtype);
-    const int64_t tile = (int64_t)kBlock * unroll_for(K);  // vectors per block iteration
+    const int64_t tile = (int64_t)kBlock * unroll_for(K, opt);  // vectors per block iteration
     const int64_t nvec = ceil_div(P, VEC);
     // Spans start at multiples of a wave's worth of vectors (1 KB of every stream), so that the
     // 64 lanes of a wave stay on whole cache lines; a block's last tile may be partial.  Kernels
@@ -284,14 +294,14 @@ int layout_plan(Plan& pl, int S, const int64_t* offsets)
 {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, pl.device) != hipSuccess) return DYNAMIX_ERR_HIP;
-    const int per_cu = stream_pass_blocks_per_cu(pl.K, pl.dtype);
+    const int per_cu = stream_pass_blocks_per_cu(pl.K, pl.dtype, pl.opt);
     if (per_cu <= 0) return DYNAMIX_ERR_HIP;
 
     Layout L;
     int64_t max_grid = (int64_t)prop.multiProcessorCount * per_cu;
     const int cap = env_int("DYNAMIX_MAX_BLOCKS", 0);   // tuning aid: another number of blocks
     if (cap > 0) max_grid = cap;
-    make_layout(pl.K, pl.dtype, pl.P, S, offsets, max_grid, L);
+    make_layout(pl.K, pl.dtype, pl.opt, pl.P, S, offsets, max_grid, L);
     pl.grid = L.grid;
     pl.pieces = (int)L.pieces.size();
     pl.n_tail = (int)L.tail_order.size();
@@ -347,20 +357,21 @@ int build_plan(Plan& pl, int S, const int64_t* offsets)
     return DYNAMIX_OK;
 }
 
-bool same_shape(const Plan& pl, int K, int dtype, int64_t P, int S, const int64_t* offsets)
+bool same_shape(const Plan& pl, int K, int dtype, int opt, int64_t P, int S, const int64_t* offsets)
 {
-    return pl.K == K && pl.dtype == dtype && pl.P == P &&
+    return pl.K == K && pl.dtype == dtype && pl.opt == opt && pl.P == P &&
            (int)pl.offsets.size() == (S > 0 ? S + 1 : 0) &&
            (S == 0 || std::memcmp(pl.offsets.data(), offsets, sizeof(int64_t) * (S + 1)) == 0);
 }
 
 // Finds or builds the plan; the caller holds g_mutex.
-int get_plan(int device, hipStream_t stream, int K, int dtype, int64_t P, int S,
+int get_plan(int device, hipStream_t stream, int K, int dtype, int opt, int64_t P, int S,
              const int64_t* offsets, Plan** out)
 {
     for (auto& up : g_plans) {
         Plan& pl = *up;
-        if (pl.device == device && pl.stream == stream && same_shape(pl, K, dtype, P, S, offsets)) {
+        if (pl.device == device && pl.stream == stream &&
+            same_shape(pl, K, dtype, opt, P, S, offsets)) {
             pl.last_use = ++g_clock;
             *out = &pl;
             return DYNAMIX_OK;
@@ -377,6 +388,7 @@ int get_plan(int device, hipStream_t stream, int K, int dtype, int64_t P, int S,
     up->stream = stream;
     up->K = K;
     up->dtype = dtype;
+    up->opt = opt;
     up->P = P;
     if (S > 0) up->offsets.assign(offsets, offsets + S + 1);
     const int rc = build_plan(*up, S, offsets);
@@ -436,7 +448,7 @@ int get_static_plan(int device, hipStream_t stream, int K, int dtype, int64_t P,
     const int rc = static_scratch_of(device, &ptr);
     if (rc != DYNAMIX_OK) return rc;
     StaticDevice& sd = g_static[device];
-    if (!sd.plan || !same_shape(*sd.plan, K, dtype, P, S, offsets)) {
+    if (!sd.plan || !same_shape(*sd.plan, K, dtype, kOptNone, P, S, offsets)) {
         auto up = std::make_unique<Plan>();
         up->device = device;
         up->K = K;
@@ -481,10 +493,23 @@ int check_shape(int32_t K, int64_t P, int32_t dtype, const int64_t* offsets, int
     return DYNAMIX_OK;
 }
 
+// The model update fused into the pass, if any: which kind, the buffers it reads and writes in
+// place, and its constants as the kernel takes them.
+struct Update {
+    int opt = kOptNone;
+    float* params = nullptr;   // also the plain SGD step of kOptNone
+    float* state1 = nullptr;
+    float* state2 = nullptr;
+    float lr = 0.f, wd = 0.f;
+    float hp[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    int32_t flags = 0;
+};
+
 int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t P, int32_t dtype,
         const int64_t* offsets, int64_t S, float* out_agg, double* out_stats, void* stream_v,
-        float* params = nullptr, float lr = 0.f, float weight_decay = 0.f, bool use_static = false)
+        const Update& up = Update(), bool use_static = false)
 {
+    float* const params = up.params;
     // ---- validation: no HIP call before this block has passed
     if (!grads || !batch_sizes || !out_stats) return DYNAMIX_ERR_NULL;
     int vrc = check_shape(K, P, dtype, offsets, S);
@@ -496,8 +521,10 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     for (int k = 0; k < K; ++k)
         if (reinterpret_cast<uintptr_t>(grads[k]) & 15u) return DYNAMIX_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(out_agg) & 15u) || (reinterpret_cast<uintptr_t>(out_stats) & 7u) ||
-        (reinterpret_cast<uintptr_t>(params) & 15u))
+        (reinterpret_cast<uintptr_t>(params) & 15u) || (reinterpret_cast<uintptr_t>(up.state1) & 15u) ||
+        (reinterpret_cast<uintptr_t>(up.state2) & 15u))
         return DYNAMIX_ERR_ALIGN;
+    if (up.opt != kOptNone && K > kKMaxOpt) return DYNAMIX_ERR_ARG;
 
     // ---- weights: B in 64-bit integers, w_k = b_k / B rounded once to fp32
     int64_t B = 0;
@@ -510,7 +537,7 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     std::lock_guard<std::mutex> lock(g_mutex);
     Plan* pl = nullptr;
     const int rc = use_static ? get_static_plan(device, stream, K, dtype, P, (int)S, offsets, &pl)
-                              : get_plan(device, stream, K, dtype, P, (int)S, offsets, &pl);
+                              : get_plan(device, stream, K, dtype, up.opt, P, (int)S, offsets, &pl);
     if (rc != DYNAMIX_OK) return rc;
     if (!pl->uploaded) {
         if (use_static) {
@@ -539,12 +566,17 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     sa.queue = pl->d_queue;
     sa.n_tail = pl->n_tail;
     sa.params = params;
-    sa.lr = lr;
-    sa.wd = weight_decay;
+    sa.lr = up.lr;
+    sa.wd = up.wd;
+    sa.state1 = up.state1;
+    sa.state2 = up.state2;
+    std::memcpy(sa.hp, up.hp, sizeof sa.hp);
+    sa.flags = up.flags;
     {
         // The interleaved tile order reads and writes 256-byte chunks: it is used when every
         // buffer starts on such a boundary (DYNAMIX_SPREAD=0 turns it off, a tuning aid).
-        uintptr_t low = reinterpret_cast<uintptr_t>(out_agg) | reinterpret_cast<uintptr_t>(params);
+        uintptr_t low = reinterpret_cast<uintptr_t>(out_agg) | reinterpret_cast<uintptr_t>(params) |
+                        reinterpret_cast<uintptr_t>(up.state1) | reinterpret_cast<uintptr_t>(up.state2);
         for (int k = 0; k < K; ++k) low |= reinterpret_cast<uintptr_t>(grads[k]);
         sa.spread = (low & 255u) == 0 && env_int("DYNAMIX_SPREAD", 1) != 0;
     }
@@ -561,7 +593,7 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     hipEvent_t* ev = nullptr;
     if (g_timing.used < g_timing.capacity) ev = &g_timing.events[3 * (size_t)g_timing.used++];
     if (ev && hipEventRecord(ev[0], stream) != hipSuccess) return DYNAMIX_ERR_HIP;
-    if (launch_stream_pass(K, dtype, pl->grid, sa, stream) != hipSuccess) return DYNAMIX_ERR_HIP;
+    if (launch_stream_pass(K, dtype, up.opt, pl->grid, sa, stream) != hipSuccess) return DYNAMIX_ERR_HIP;
     // From here on the tail counter is in use; only the final reduction sets it back.  Should
     // that not get enqueued, the tables (with a zero counter) are uploaded again next time.
     pl->uploaded = false;
@@ -599,7 +631,7 @@ int dynamix_grad_aggregate_stats_static(const void* const* grads, const int32_t*
 {
     try {
         return dynamix::run(grads, batch_sizes, K, P, dtype, segment_offsets, num_segments, out_agg,
-                            out_stats, stream, nullptr, 0.f, 0.f, /*use_static=*/true);
+                            out_stats, stream, dynamix::Update(), /*use_static=*/true);
     } catch (const std::bad_alloc&) {
         return DYNAMIX_ERR_NOMEM;
     } catch (...) {
@@ -616,8 +648,79 @@ int dynamix_grad_aggregate_stats_sgd(const void* const* grads, const int32_t* ba
     if (!params) return DYNAMIX_ERR_NULL;
     if (!(lr == lr) || !(weight_decay == weight_decay)) return DYNAMIX_ERR_ARG;   // NaN
     try {
+        dynamix::Update up;
+        up.params = params;
+        up.lr = lr;
+        up.wd = weight_decay;
         return dynamix::run(grads, batch_sizes, K, P, dtype, segment_offsets, num_segments, nullptr,
-                            out_stats, stream, params, lr, weight_decay);
+                            out_stats, stream, up);
+    } catch (const std::bad_alloc&) {
+        return DYNAMIX_ERR_NOMEM;
+    } catch (...) {
+        return DYNAMIX_ERR_HIP;
+    }
+}
+
+int dynamix_grad_aggregate_stats_sgd_momentum(const void* const* grads, const int32_t* batch_sizes,
+                                              int32_t K, int64_t P, int32_t dtype,
+                                              const int64_t* segment_offsets, int64_t num_segments,
+                                              float* params, float* momentum_buf, float lr,
+                                              float weight_decay, float momentum, int32_t nesterov,
+                                              double* out_stats, void* stream)
+{
+    if (!params || !momentum_buf) return DYNAMIX_ERR_NULL;
+    if (!(lr == lr) || !(weight_decay == weight_decay) || !(momentum == momentum))
+        return DYNAMIX_ERR_ARG;   // NaN
+    try {
+        dynamix::Update up;
+        up.opt = dynamix::kOptMomentum;
+        up.params = params;
+        up.state1 = momentum_buf;
+        up.lr = lr;
+        up.wd = weight_decay;
+        up.hp[0] = momentum;
+        up.flags = nesterov ? 1 : 0;
+        return dynamix::run(grads, batch_sizes, K, P, dtype, segment_offsets, num_segments, nullptr,
+                            out_stats, stream, up);
+    } catch (const std::bad_alloc&) {
+        return DYNAMIX_ERR_NOMEM;
+    } catch (...) {
+        return DYNAMIX_ERR_HIP;
+    }
+}
+
+int dynamix_grad_aggregate_stats_adam(const void* const* grads, const int32_t* batch_sizes, int32_t K,
+                                      int64_t P, int32_t dtype, const int64_t* segment_offsets,
+                                      int64_t num_segments, float* params, float* exp_avg,
+                                      float* exp_avg_sq, float lr, float beta1, float beta2, float eps,
+                                      float weight_decay, int32_t decoupled, int64_t step,
+                                      double* out_stats, void* stream)
+{
+    if (!params || !exp_avg || !exp_avg_sq) return DYNAMIX_ERR_NULL;
+    if (!(lr == lr) || !(weight_decay == weight_decay) || !(eps == eps) || step < 1 ||
+        !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
+        return DYNAMIX_ERR_ARG;
+    try {
+        // the constants of the step, worked out once in double and rounded to fp32
+        const double c1 = 1.0 - std::pow((double)beta1, (double)step);
+        const double c2 = 1.0 - std::pow((double)beta2, (double)step);
+        dynamix::Update up;
+        up.opt = dynamix::kOptAdam;
+        up.params = params;
+        up.state1 = exp_avg;
+        up.state2 = exp_avg_sq;
+        up.lr = lr;
+        up.wd = decoupled ? 0.f : weight_decay;
+        up.hp[0] = beta1;
+        up.hp[1] = (float)(1.0 - (double)beta1);
+        up.hp[2] = beta2;
+        up.hp[3] = (float)(1.0 - (double)beta2);
+        up.hp[4] = (float)(1.0 / std::sqrt(c2));
+        up.hp[5] = eps;
+        up.hp[6] = (float)((double)lr / c1);
+        up.hp[7] = decoupled ? (float)(1.0 - (double)lr * (double)weight_decay) : 1.f;
+        return dynamix::run(grads, batch_sizes, K, P, dtype, segment_offsets, num_segments, nullptr,
+                            out_stats, stream, up);
     } catch (const std::bad_alloc&) {
         return DYNAMIX_ERR_NOMEM;
     } catch (...) {
@@ -674,7 +777,8 @@ int64_t dynamix_plan_describe(int32_t K, int64_t P, int32_t dtype, const int64_t
     if (max_blocks < 1 || capacity < 0 || (capacity > 0 && !pieces_out)) return -DYNAMIX_ERR_ARG;
     try {
         dynamix::Layout L;
-        dynamix::make_layout(K, dtype, P, (int)num_segments, segment_offsets, max_blocks, L);
+        dynamix::make_layout(K, dtype, dynamix::kOptNone, P, (int)num_segments, segment_offsets,
+                             max_blocks, L);
         const int64_t n = (int64_t)L.pieces.size();
         for (int64_t i = 0; i < n && i < capacity; ++i) {
             const dynamix::Piece& pc = L.pieces[i];

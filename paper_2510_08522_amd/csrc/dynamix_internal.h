@@ -16,10 +16,22 @@ constexpr int kHead = 8;         // scalars in front of the per-worker entries o
 enum : int { kF32 = 0, kBF16 = 1, kF16 = 2 };
 constexpr int kDtypes = 3;
 
+// What the streaming pass does with the aggregate: write it (or apply plain SGD to the parameters
+// in place of the write), or carry optimizer state through the same pass.  An update with state
+// writes 1 + (number of state vectors) streams and reads them first.
+enum : int { kOptNone = 0, kOptMomentum = 1, kOptAdam = 2 };
+constexpr int kOpts = 3;
+constexpr int kKMaxOpt = 24;     // most workers for the updates with state (register budget)
+constexpr int out_streams(int opt) { return 1 + opt; }
+
 // Vectors (16-byte loads) per thread and block iteration.  Small K gets several so that each
 // lane keeps enough independent loads in flight; K x U x 4 data registers stay live until the
-// aggregate of the vector is known.
-constexpr int unroll_for(int K) { return K <= 2 ? 8 : K <= 8 ? 4 : K <= 16 ? 2 : 1; }
+// aggregate of the vector is known.  The updates with state also hold a vector of every state
+// stream per unrolled vector, and park two or three streams instead of one, so they unroll less.
+constexpr int unroll_for(int K, int opt = kOptNone)
+{
+    return opt == kOptNone ? (K <= 2 ? 8 : K <= 8 ? 4 : K <= 16 ? 2 : 1) : (K <= 2 ? 4 : K <= 8 ? 2 : 1);
+}
 
 // 32-bit words a lane loads at a time: four (128-bit loads) up to 32 workers, two up to 48, one
 // above, so that the K vectors of a lane plus the 2K+1 running sums stay within the 256 vector
@@ -58,6 +70,13 @@ struct StreamArgs {
     int32_t n_tail;
     float* params;               // fused model update: p <- p - lr (G + wd p) in place; else null
     float lr, wd;
+    // Updates with state (kOptMomentum: state1 = momentum buffer; kOptAdam: state1, state2 = first
+    // and second moment), read and written in place like params.  hp: the update's constants,
+    // prepared on the host (see optimizer_constants in api.hip); flags: bit 0 Nesterov / decoupled.
+    float* state1;
+    float* state2;
+    float hp[8];
+    int32_t flags;
     // Non-zero: every worker buffer and the output start at a multiple of 256 bytes, and the
     // kernel may take its tiles as 256-byte chunks of several 4 KB units (see stream_pass.h).
     int32_t spread;
@@ -76,20 +95,29 @@ struct FinalArgs {
     int32_t K;
 };
 
-// Enqueue the streaming pass for (K, dtype); returns hipErrorInvalidValue for an unknown pair.
-hipError_t launch_stream_pass(int K, int dtype, int grid, const StreamArgs& a, hipStream_t s);
+// Enqueue the streaming pass for (K, dtype, opt); returns hipErrorInvalidValue for an unknown
+// combination.
+hipError_t launch_stream_pass(int K, int dtype, int opt, int grid, const StreamArgs& a, hipStream_t s);
 // Resident blocks per compute unit of that kernel (0 on error).
-int stream_pass_blocks_per_cu(int K, int dtype);
+int stream_pass_blocks_per_cu(int K, int dtype, int opt);
 hipError_t launch_final_reduce(int records, const FinalArgs& a, hipStream_t s);
 
-// One instantiation unit per dtype and group of eight K: launch_stream_pass_<dtype>_<first K>.
-#define DYNAMIX_DECLARE_UNIT(DT, LO)                                                        \
-    hipError_t launch_stream_pass_##DT##_##LO(int K, int grid, const StreamArgs& a, hipStream_t s); \
-    int occupancy_stream_pass_##DT##_##LO(int K);
-#define DYNAMIX_FOR_EACH_UNIT(X) \
-    X(0, 1) X(0, 9) X(0, 17) X(0, 25) X(0, 33) X(0, 41) X(0, 49) X(0, 57) \
-    X(1, 1) X(1, 9) X(1, 17) X(1, 25) X(1, 33) X(1, 41) X(1, 49) X(1, 57) \
-    X(2, 1) X(2, 9) X(2, 17) X(2, 25) X(2, 33) X(2, 41) X(2, 49) X(2, 57)
-DYNAMIX_FOR_EACH_UNIT(DYNAMIX_DECLARE_UNIT)
+// One instantiation unit per update kind, dtype and group of eight K:
+// launch_stream_pass_<opt>_<dtype>_<first K>.
+#define DYNAMIX_DECLARE_UNIT(OPT, DT, LO)                                                          \
+    hipError_t launch_stream_pass_##OPT##_##DT##_##LO(int K, int grid, const StreamArgs& a, hipStream_t s); \
+    int occupancy_stream_pass_##OPT##_##DT##_##LO(int K);
+#define DYNAMIX_FOR_EACH_PLAIN_UNIT(X, DT) \
+    X(0, DT, 1) X(0, DT, 9) X(0, DT, 17) X(0, DT, 25) X(0, DT, 33) X(0, DT, 41) X(0, DT, 49) X(0, DT, 57)
+#define DYNAMIX_FOR_EACH_STATE_UNIT(X, OPT, DT) X(OPT, DT, 1) X(OPT, DT, 9) X(OPT, DT, 17)
+DYNAMIX_FOR_EACH_PLAIN_UNIT(DYNAMIX_DECLARE_UNIT, 0)
+DYNAMIX_FOR_EACH_PLAIN_UNIT(DYNAMIX_DECLARE_UNIT, 1)
+DYNAMIX_FOR_EACH_PLAIN_UNIT(DYNAMIX_DECLARE_UNIT, 2)
+DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_DECLARE_UNIT, 1, 0)
+DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_DECLARE_UNIT, 1, 1)
+DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_DECLARE_UNIT, 1, 2)
+DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_DECLARE_UNIT, 2, 0)
+DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_DECLARE_UNIT, 2, 1)
+DYNAMIX_FOR_EACH_STATE_UNIT(DYNAMIX_DECLARE_UNIT, 2, 2)
 
 }  // namespace dynamix

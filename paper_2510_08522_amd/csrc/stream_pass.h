@@ -173,7 +173,7 @@ __device__ __forceinline__ uint32_t from_acc(uint32_t a)
 // bytes added for the second half of a vector.
 constexpr int kMaskedStore = 0x7fff0000;
 
-template <int K, int DT, int U>
+template <int K, int DT, int U, int NO>
 struct Shape {
     static constexpr int kLW = load_words_for(K);                  // words per lane and load
     static constexpr int kVB = kLW * 4;                            // bytes per lane and load
@@ -181,37 +181,64 @@ struct Shape {
     static constexpr int kSize = DT == kF32 ? 4 : 2;               // bytes per element
     static constexpr int kQ = kVec / kLW;                          // LW-word pieces of G per vector
     static constexpr int kSlots = kStageBytes / (kBlock * kVB);    // LW-word slots per thread
-    static constexpr int kTiles = kSlots / (U * kQ);               // tiles the LDS holds
+    static constexpr int kPerTile = U * kQ * NO;                   // slots a parked tile takes (NO streams)
+    static constexpr int kTiles = kSlots / kPerTile;               // tiles the LDS holds
     // a second, smaller bank in what the first leaves of the 256 accumulation registers
-    static constexpr int kTiles2 = (256 - kTiles * U * kQ * kLW) / (U * kQ * kLW);
+    static constexpr int kTiles2 = (256 - kTiles * kPerTile * kLW) / (kPerTile * kLW);
     static_assert(kTiles >= 1, "a tile of G must fit the staging area");
 };
 
-template <int K, int DT, int U>
+template <int K, int DT, int U, int OPT>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) void stream_pass_kernel(
     const StreamArgs a)
 {
-    typedef Shape<K, DT, U> Sh;
+    constexpr int NO = out_streams(OPT);   // streams written (and, but for the plain aggregate, read first)
+    typedef Shape<K, DT, U, NO> Sh;
     typedef Words<Sh::kLW> Wd;
     typedef typename Wd::type wvec;
     constexpr int LW = Sh::kLW, VB = Sh::kVB, VEC = Sh::kVec, Q = Sh::kQ, NB = Sh::kTiles;
     constexpr int NB2 = Sh::kTiles2;
     constexpr int W = 2 * K + 1;
     constexpr int64_t TILE = (int64_t)kBlock * U;   // vectors per block iteration
-    __shared__ wvec stage[NB * U * Q][kBlock];
+    __shared__ wvec stage[NB * U * Q * NO][kBlock];
     __shared__ float wave_part[kWaves][W];
 
     const int tid = threadIdx.x;
     const int p_first = a.block_range[2 * blockIdx.x];
     const int p_last = a.block_range[2 * blockIdx.x + 1];
     // What is written per element: the aggregate G, or, with the fused model update, the new
-    // parameter p - lr (G + wd p) over the old one; nothing in statistics-only calls.
-    const bool fused = a.params != nullptr;
+    // parameter p - lr (G + wd p) over the old one; nothing in statistics-only calls.  The updates
+    // with state (momentum, Adam) read and write the parameters and one or two state vectors.
+    const bool fused = OPT != kOptNone || a.params != nullptr;
     float* const out = fused ? a.params : a.out_agg;
-    const bool want_agg = out != nullptr;
+    const bool want_agg = OPT != kOptNone || out != nullptr;
     const float neg_lr = -a.lr, wd = a.wd;
-    auto updated = [&](float g, float p) {
-        return fused ? __builtin_fmaf(neg_lr, __builtin_fmaf(wd, p, g), p) : g;
+    // stream s of the output (the same buffer is its input where there is one)
+    auto out_ptr = [&](int s) -> float* { return s == 0 ? out : s == 1 ? a.state1 : a.state2; };
+    // One element: the aggregate g and the old values in[] of the NO streams give the new ones.
+    auto update = [&](float g, const float (&in)[NO], float (&o)[NO]) {
+        if constexpr (OPT == kOptNone) {
+            o[0] = fused ? __builtin_fmaf(neg_lr, __builtin_fmaf(wd, in[0], g), in[0]) : g;
+        } else if constexpr (OPT == kOptMomentum) {
+            // g' = G + wd p;  buf' = mu buf + g';  p' = p - lr (Nesterov: g' + mu buf', else buf')
+            const float mu = a.hp[0];
+            const float gp = __builtin_fmaf(wd, in[0], g);
+            const float b = __builtin_fmaf(mu, in[1], gp);
+            const float step = (a.flags & 1) ? __builtin_fmaf(mu, b, gp) : b;
+            o[0] = __builtin_fmaf(neg_lr, step, in[0]);
+            o[1] = b;
+        } else {
+            // Adam.  hp: beta1, 1 - beta1, beta2, 1 - beta2, 1 / sqrt(1 - beta2^t), eps,
+            // lr / (1 - beta1^t), and the factor on p (1 - lr wd when the decay is decoupled, else
+            // 1; wd is then zero in the gradient)
+            const float gp = __builtin_fmaf(wd, in[0], g);
+            const float m = __builtin_fmaf(a.hp[0], in[1], a.hp[1] * gp);
+            const float v = __builtin_fmaf(a.hp[2], in[2], (a.hp[3] * gp) * gp);
+            const float denom = __builtin_fmaf(__builtin_sqrtf(v), a.hp[4], a.hp[5]);
+            o[0] = __builtin_fmaf(-a.hp[6], m / denom, in[0] * a.hp[7]);
+            o[1] = m;
+            o[2] = v;
+        }
     };
 
     // The block's own pieces, then pieces of the shared tail for as long as there are any: one
@@ -359,17 +386,31 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 #pragma unroll
             for (int c = 0; c < VEC; ++c) A = __builtin_fmaf(Ge[c], Ge[c], A);
             if (want_b) {
-                const __amdgpu_buffer_rsrc_t r = tile_rsrc(out_b, v * (VEC * 4), VEC * 4);
+                __amdgpu_buffer_rsrc_t r[NO];
+                r[0] = tile_rsrc(out_b, v * (VEC * 4), VEC * 4);
+                if constexpr (NO > 1) r[1] = tile_rsrc(a.state1, v * (VEC * 4), VEC * 4);
+                if constexpr (NO > 2) r[2] = tile_rsrc(a.state2, v * (VEC * 4), VEC * 4);
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) {
                     const int oc = off[c] == kMasked ? kMasked : c * 4;
-                    float res = Ge[c];
-                    if (fused_b) {
-                        const float pc_old =
-                            __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, oc, 0, 0));
-                        res = __builtin_fmaf(neg_lr, __builtin_fmaf(wd, pc_old, Ge[c]), pc_old);
+                    if constexpr (OPT == kOptNone) {
+                        float res = Ge[c];
+                        if (fused_b) {
+                            const float pc_old =
+                                __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r[0], oc, 0, 0));
+                            res = __builtin_fmaf(neg_lr, __builtin_fmaf(wd, pc_old, Ge[c]), pc_old);
+                        }
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(res), r[0], oc, 0, 0);
+                    } else {
+                        float in[NO], o[NO];
+#pragma unroll
+                        for (int s = 0; s < NO; ++s)
+                            in[s] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r[s], oc, 0, 0));
+                        update(Ge[c], in, o);
+#pragma unroll
+                        for (int s = 0; s < NO; ++s)
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(o[s]), r[s], oc, 0, 0);
                     }
-                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(res), r, oc, 0, 0);
                 }
             }
 #pragma unroll
@@ -459,7 +500,22 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             // The K vectors of every lane.  A tile is always loaded one iteration ahead: by
             // pass 2 of the tile before it, or here for the first one.
             wvec x[U][K];
-            wvec xp[U][Q];   // the parameters of the tile (fused update only; else never read)
+            // the old values of the NO output streams for the tile: the parameters (fused updates
+            // only; else never read, through a descriptor of length zero) and the optimizer state
+            wvec xs[NO][U][Q];
+            auto load_streams = [&](const Where& w, int tw) {
+#pragma unroll
+                for (int s = 0; s < NO; ++s) {
+                    const __amdgpu_buffer_rsrc_t rp = tile_rsrc(
+                        s == 0 ? a.params : out_ptr(s), w.v * (VEC * 4), fused ? w.count * (VEC * 4) : 0);
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+#pragma unroll
+                        for (int h = 0; h < Q; ++h)
+                            xs[s][u][h] = Wd::template load<kLoadPolicy>(
+                                rp, lane_vec(tw, u) * (VEC * 4) + VB * h);
+                }
+            };
             {
                 const Where w0 = where(0);
 #pragma unroll
@@ -468,14 +524,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                     for (int k = 0; k < K; ++k)
                         x[u][k] = Wd::template load<kLoadPolicy>(
                             tile_rsrc(a.g[k], w0.v * VB, w0.count * VB), lane_vec(0, u) * VB);
-                const __amdgpu_buffer_rsrc_t rp =
-                    tile_rsrc(a.params, w0.v * (VEC * 4), fused ? w0.count * (VEC * 4) : 0);
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-#pragma unroll
-                    for (int h = 0; h < Q; ++h)
-                        xp[u][h] = Wd::template load<kLoadPolicy>(
-                            rp, lane_vec(0, u) * (VEC * 4) + VB * h);
+                load_streams(w0, 0);
             }
             int staged = 0;            // tiles parked in LDS
             int t_staged = 0;          // first of them
@@ -497,7 +546,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             // the period: four fifths of the time a block takes to fill its staging at full speed
             // (a tile at 26.5 GB/s per compute unit), in ticks of the 100 MHz clock
             constexpr uint32_t kFlushPeriod = (uint32_t)(
-                0.8 * kStagedMax * ((double)(kBlock * U) * (K * VB + VEC * 4) / 265.0));
+                0.8 * kStagedMax *
+                ((double)(kBlock * U) * (K * VB + (OPT == kOptNone ? 1 : 2 * NO) * VEC * 4) / 265.0));
             constexpr int kNever = 0x7fffffff;
             __shared__ int wave0_progress, flush_after;
             // (only where a piece fills the staging several times: one that fits it once is
@@ -516,8 +566,8 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             }
             // the register banks (accumulation registers): NB and NB2 more tiles, parked before
             // those in the LDS
-            uint32_t bank[NB * U * Q * LW];
-            uint32_t bank2[(NB2 > 0 ? NB2 : 1) * U * Q * LW];
+            uint32_t bank[NB * U * Q * NO * LW];
+            uint32_t bank2[(NB2 > 0 ? NB2 : 1) * U * Q * NO * LW];
             int t_bank = 0, t_bank2 = 0;   // first tile of each bank
             bool more = true;
             // 16-bit inputs: a vector of G is twice the width of a store, and a lane that wrote
@@ -556,16 +606,23 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 for (int u = 0; u < U; ++u) {
                     pass1(x[u], G[u], kw);
                     if (want_agg) {
-                        // park G (fp32 inputs: every thread later reads back only what it wrote
-                        // itself; 16-bit inputs: see kSwap)
+                        // park what will be written (fp32 inputs: every thread later reads back
+                        // only what it wrote itself; 16-bit inputs: see kSwap)
 #pragma unroll
                         for (int h = 0; h < Q; ++h) {
-                            wvec q;
+                            wvec q[NO];
 #pragma unroll
-                            for (int c = 0; c < LW; ++c)
-                                q[c] = __float_as_uint(
-                                    updated(G[u][LW * h + c], __uint_as_float(xp[u][h][c])));
-                            stage[(staged * U + u) * Q + h][tid] = q;
+                            for (int c = 0; c < LW; ++c) {
+                                float in[NO], o[NO];
+#pragma unroll
+                                for (int s = 0; s < NO; ++s) in[s] = __uint_as_float(xs[s][u][h][c]);
+                                update(G[u][LW * h + c], in, o);
+#pragma unroll
+                                for (int s = 0; s < NO; ++s) q[s][c] = __float_as_uint(o[s]);
+                            }
+#pragma unroll
+                            for (int s = 0; s < NO; ++s)
+                                stage[((staged * U + u) * NO + s) * Q + h][tid] = q[s];
                         }
                     }
                 }
@@ -611,8 +668,11 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                         asm volatile("" : "+v"(lane_f));
                         // one descriptor over the whole body for the stores (a piece has at most
                         // 2^18 vectors, so byte offsets inside it fit the 32-bit lane offset)
-                        const __amdgpu_buffer_rsrc_t r = tile_rsrc(
-                            out, body_begin * (VEC * 4), (int)(body_vectors * (VEC * 4)));
+                        __amdgpu_buffer_rsrc_t r[NO];
+#pragma unroll
+                        for (int s = 0; s < NO; ++s)
+                            r[s] = tile_rsrc(out_ptr(s), body_begin * (VEC * 4),
+                                             (int)(body_vectors * (VEC * 4)));
                         // where this lane's h-th store of a tile goes (see kSwap)
                         auto out_off = [&](int tj, int u, int h) -> int {
                             const int tq = tj - has_pre;
@@ -631,13 +691,15 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                                 for (int u = 0; u < U; ++u)
 #pragma unroll
                                     for (int h = 0; h < Q; ++h)
-                                    {
-                                        wvec t;
 #pragma unroll
-                                        for (int c = 0; c < LW; ++c)
-                                            t[c] = from_acc(bank[((j * U + u) * Q + h) * LW + c]);
-                                        Wd::template store<kStorePolicy>(t, r, out_off(tj, u, h));
-                                    }
+                                        for (int s = 0; s < NO; ++s) {
+                                            wvec t;
+#pragma unroll
+                                            for (int c = 0; c < LW; ++c)
+                                                t[c] = from_acc(
+                                                    bank[((((j * U + u) * NO + s) * Q) + h) * LW + c]);
+                                            Wd::template store<kStorePolicy>(t, r[s], out_off(tj, u, h));
+                                        }
                             }
                         }
                         if constexpr (kMode == 2) {
@@ -648,13 +710,15 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                                 for (int u = 0; u < U; ++u)
 #pragma unroll
                                     for (int h = 0; h < Q; ++h)
-                                    {
-                                        wvec t;
 #pragma unroll
-                                        for (int c = 0; c < LW; ++c)
-                                            t[c] = from_acc(bank2[((j * U + u) * Q + h) * LW + c]);
-                                        Wd::template store<kStorePolicy>(t, r, out_off(tj, u, h));
-                                    }
+                                        for (int s = 0; s < NO; ++s) {
+                                            wvec t;
+#pragma unroll
+                                            for (int c = 0; c < LW; ++c)
+                                                t[c] = from_acc(
+                                                    bank2[((((j * U + u) * NO + s) * Q) + h) * LW + c]);
+                                            Wd::template store<kStorePolicy>(t, r[s], out_off(tj, u, h));
+                                        }
                             }
                         }
                         for (int j = 0; j < staged; ++j) {
@@ -663,9 +727,12 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                             for (int u = 0; u < U; ++u)
 #pragma unroll
                                 for (int h = 0; h < Q; ++h)
-                                    Wd::template store<kStorePolicy>(
-                                        stage[(j * U + u) * Q + src_half(tid, h)][src_lane(tid, h)],
-                                        r, out_off(tj, u, h));
+#pragma unroll
+                                    for (int s = 0; s < NO; ++s)
+                                        Wd::template store<kStorePolicy>(
+                                            stage[((j * U + u) * NO + s) * Q + src_half(tid, h)]
+                                                 [src_lane(tid, h)],
+                                            r[s], out_off(tj, u, h));
                         }
                         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                         __syncthreads();
@@ -695,16 +762,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                             tile_rsrc(kReloadWeights ? kg[k] : a.g[k], wn.v * VB, next_bytes), pf_off);
                     }
                 }
-                {
-                    const __amdgpu_buffer_rsrc_t rp = tile_rsrc(
-                        a.params, wn.v * (VEC * 4), fused ? wn.count * (VEC * 4) : 0);
-#pragma unroll
-                    for (int u = 0; u < U; ++u)
-#pragma unroll
-                        for (int h = 0; h < Q; ++h)
-                            xp[u][h] = Wd::template load<kLoadPolicy>(
-                                rp, lane_vec(tn, u) * (VEC * 4) + VB * h);
-                }
+                load_streams(wn, tn);
                 t = tn;
             };
             // The banks are used up to K = 44.  Above, the loop itself needs all 256 vector
@@ -723,7 +781,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                 // again
                 if (kSwap) __syncthreads();
 #pragma unroll
-                for (int j = 0; j < NB * U; ++j)
+                for (int j = 0; j < NB * U * NO; ++j)   // (tile, vector, stream) in parking order
 #pragma unroll
                     for (int h = 0; h < Q; ++h) {
                         const wvec t = stage[j * Q + src_half(tid, h)][src_lane(tid, h)];
@@ -745,7 +803,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
                     // the second, smaller bank
                     if (kSwap) __syncthreads();
 #pragma unroll
-                    for (int j = 0; j < NB2 * U; ++j)
+                    for (int j = 0; j < NB2 * U * NO; ++j)
 #pragma unroll
                         for (int h = 0; h < Q; ++h) {
                             const wvec t = stage[j * Q + src_half(tid, h)][src_lane(tid, h)];
@@ -798,19 +856,19 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
 
 // Switch over K for one dtype; instantiated in one translation unit per dtype and K range so
 // that the build can compile them in parallel.
-template <int DT, int K>
+template <int DT, int K, int OPT>
 hipError_t launch_one(int grid, const StreamArgs& a, hipStream_t s)
 {
-    stream_pass_kernel<K, DT, unroll_for(K)><<<dim3(grid), dim3(kBlock), 0, s>>>(a);
+    stream_pass_kernel<K, DT, unroll_for(K, OPT), OPT><<<dim3(grid), dim3(kBlock), 0, s>>>(a);
     return hipGetLastError();
 }
 
-template <int DT, int K>
+template <int DT, int K, int OPT>
 int occupancy_one()
 {
     int nb = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(
-            &nb, stream_pass_kernel<K, DT, unroll_for(K)>, kBlock, 0) != hipSuccess)
+            &nb, stream_pass_kernel<K, DT, unroll_for(K, OPT), OPT>, kBlock, 0) != hipSuccess)
         return 0;
     return nb;
 }

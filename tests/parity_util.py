@@ -92,3 +92,71 @@ def compare_sgd(got, ref, p0, agg_ref, lr, is_bf16=False, where=""):
     scale = np.abs(np.asarray(p0, dtype=np.float64)) + abs(lr) * np.abs(agg_ref)
     assert np.linalg.norm(got - ref) <= tol * np.linalg.norm(ref), where
     assert (np.abs(got - ref) <= 4e-7 * scale + tol * abs(lr) * np.abs(agg_ref).max()).all(), where
+
+
+EPS32 = 2.0 ** -24      # unit roundoff of fp32
+
+
+def aggregate_error_bound(host_grads, batch_sizes, widen):
+    """Element-wise bound on the error of the fp32 aggregate: K fused multiply-adds in worker
+    order with weights rounded once give |dG_i| <= (K + 2) 2^-24 sum_k w_k |g_ki|.  host_grads are
+    the stored inputs, `widen` turns one of them into float64."""
+    K = len(host_grads)
+    w = np.asarray(batch_sizes, dtype=np.float64) / float(np.sum(batch_sizes))
+    s = np.zeros(len(host_grads[0]), dtype=np.float64)
+    for k in range(K):
+        s += w[k] * np.abs(widen(host_grads[k]))
+    return (K + 2) * EPS32 * s
+
+
+def compare_momentum(got_p, got_b, ref_p, ref_b, p0, b0, agg_ref, dg, lr, wd, mu, nesterov,
+                     is_bf16=False, where=""):
+    """Fused SGD-with-momentum step against the oracle's.  dg: element-wise error bound of the
+    aggregate.  The buffer is two fp32 fused multiply-adds on top of G, the parameter one or two
+    more; each rounds at most half an ulp of its result, bounded here by the sum of the magnitudes
+    of its operands."""
+    tol = 1e-3 if is_bf16 else 1e-5
+    p0, b0 = np.asarray(p0, dtype=np.float64), np.asarray(b0, dtype=np.float64)
+    got_p, got_b = np.asarray(got_p, dtype=np.float64), np.asarray(got_b, dtype=np.float64)
+    g_mag = np.abs(agg_ref) + abs(wd) * np.abs(p0)
+    b_mag = abs(mu) * np.abs(b0) + g_mag
+    bound_b = 3 * EPS32 * b_mag + dg
+    assert (np.abs(got_b - ref_b) <= bound_b).all(), (where, "momentum buffer")
+    assert np.linalg.norm(got_b - ref_b) <= tol * np.linalg.norm(ref_b), (where, "buffer 2-norm")
+    step_mag = (g_mag + abs(mu) * b_mag) if nesterov else b_mag
+    amp = (1 + abs(mu)) if nesterov else 1.0
+    bound_p = 2 * EPS32 * (np.abs(p0) + abs(lr) * step_mag) + abs(lr) * (amp * bound_b + 2 * EPS32 * step_mag)
+    assert (np.abs(got_p - ref_p) <= bound_p).all(), (where, "parameters")
+    assert np.linalg.norm(got_p - ref_p) <= tol * np.linalg.norm(ref_p), (where, "parameters 2-norm")
+
+
+def compare_adam(got, ref, p0, m0, v0, agg_ref, dg, lr, beta1, beta2, eps, wd, decoupled, step,
+                 is_bf16=False, where=""):
+    """Fused Adam step against the oracle's.  got, ref: (params, exp_avg, exp_avg_sq).  With
+    g' the gradient after L2 decay, D = sqrt(v' / (1 - beta2^t)) + eps and s = lr / (1 - beta1^t),
+    an error dg in g' moves m' by (1 - beta1) dg, v' by at most 2 (1 - beta2) |g'| dg + (1 - beta2) dg^2,
+    its root by at most sqrt(1 - beta2) dg, and the update s m' / D by at most
+    s dg ((1 - beta1) / D + |m'| sqrt((1 - beta2) / (1 - beta2^t)) / D^2); on top come the roundings
+    of the fp32 operations themselves (a handful of half-ulps of each result)."""
+    tol = 1e-3 if is_bf16 else 1e-5
+    p0, m0, v0 = (np.asarray(x, dtype=np.float64) for x in (p0, m0, v0))
+    gp, gm, gv = (np.asarray(x, dtype=np.float64) for x in got)
+    rp, rm, rv = ref
+    c1, c2 = 1.0 - beta1 ** step, 1.0 - beta2 ** step
+    s = lr / c1
+    g = agg_ref if decoupled else agg_ref + wd * p0
+    dg = dg + 2 * EPS32 * (np.abs(agg_ref) + abs(wd) * np.abs(p0))
+    bound_m = 3 * EPS32 * (beta1 * np.abs(m0) + (1 - beta1) * np.abs(g)) + (1 - beta1) * dg
+    assert (np.abs(gm - rm) <= bound_m).all(), (where, "exp_avg")
+    bound_v = 4 * EPS32 * rv + (1 - beta2) * (2 * np.abs(g) * dg + dg * dg)
+    assert (np.abs(gv - rv) <= bound_v).all(), (where, "exp_avg_sq")
+    D = np.sqrt(rv / c2) + eps
+    upd = s * np.abs(rm) / D
+    droot = np.sqrt(1 - beta2) * dg + 3 * EPS32 * np.sqrt(rv)       # error of sqrt(v')
+    bound_u = 8 * EPS32 * upd + s * (bound_m / D + np.abs(rm) * droot / np.sqrt(c2) / (D * D))
+    bound_p = 3 * EPS32 * (np.abs(p0) + upd) + bound_u
+    assert (np.abs(gp - rp) <= bound_p).all(), (where, "parameters",
+                                                 float(np.max(np.abs(gp - rp) / bound_p)))
+    assert np.linalg.norm(gm - rm) <= tol * np.linalg.norm(rm), (where, "exp_avg 2-norm")
+    assert np.linalg.norm(gv - rv) <= tol * np.linalg.norm(rv), (where, "exp_avg_sq 2-norm")
+    assert np.linalg.norm(gp - rp) <= tol * np.linalg.norm(rp), (where, "parameters 2-norm")

@@ -93,6 +93,32 @@ def test_validation_precedes_any_device_work():
     assert raw(ok_p, ok_b, 2, 100, stats=ST + 4) == B.DYNAMIX_ERR_ALIGN
 
 
+def test_stateful_update_validation_precedes_any_device_work():
+    lib = B.load()
+    K = 3
+    ptrs = (ctypes.c_void_p * K)(A16, A16 + 64, A16 + 128)
+    b = (ctypes.c_int32 * K)(32, 64, 96)
+
+    def momentum(params=A16 + 256, buf=A16 + 512, lr=0.1, k=K, pp=ptrs, bb=b):
+        return lib.dynamix_grad_aggregate_stats_sgd_momentum(pp, bb, k, 100, 0, None, 0, params, buf,
+                                                             lr, 0.0, 0.9, 0, ST, None)
+
+    def adam(params=A16 + 256, m=A16 + 512, v=A16 + 768, lr=1e-3, b1=0.9, b2=0.999, step=1):
+        return lib.dynamix_grad_aggregate_stats_adam(ptrs, b, K, 100, 0, None, 0, params, m, v, lr, b1,
+                                                     b2, 1e-8, 0.0, 0, step, ST, None)
+
+    assert momentum(params=None) == B.DYNAMIX_ERR_NULL and momentum(buf=None) == B.DYNAMIX_ERR_NULL
+    assert momentum(lr=float("nan")) == B.DYNAMIX_ERR_ARG
+    assert momentum(buf=A16 + 516) == B.DYNAMIX_ERR_ALIGN
+    many = B.DYNAMIX_K_MAX_STATEFUL + 1
+    assert momentum(k=many, pp=(ctypes.c_void_p * many)(*[A16 + 64 * i for i in range(many)]),
+                    bb=(ctypes.c_int32 * many)(*[32] * many)) == B.DYNAMIX_ERR_ARG
+    assert adam(m=None) == B.DYNAMIX_ERR_NULL and adam(v=None) == B.DYNAMIX_ERR_NULL
+    assert adam(step=0) == B.DYNAMIX_ERR_ARG and adam(b1=1.0) == B.DYNAMIX_ERR_ARG
+    assert adam(b2=-0.1) == B.DYNAMIX_ERR_ARG and adam(lr=float("nan")) == B.DYNAMIX_ERR_ARG
+    assert adam(v=A16 + 772) == B.DYNAMIX_ERR_ALIGN
+
+
 def test_segment_offsets_validation():
     p, b = [A16, A16 + 64], [32, 64]
     bad = B.DYNAMIX_ERR_SEGMENTS
@@ -283,8 +309,11 @@ def test_build_check_of_register_allocation():
     assert [Bd._bank_registers(K, d, U) for K, d, U in
             [(1, 0, 8), (8, 0, 4), (16, 1, 2), (32, 0, 1), (32, 2, 1), (33, 0, 1), (44, 1, 1), (45, 0, 1),
              (64, 1, 1)]] == [256, 256, 256, 256, 256, 256, 256, 0, 0]
+    # the updates with state park two or three streams per tile
+    assert [Bd._bank_registers(K, d, U, o) for K, d, U, o in
+            [(24, 0, 1, 2), (24, 1, 1, 2), (2, 1, 4, 2), (8, 1, 2, 2), (8, 0, 2, 1)]] == [252, 240, 192, 240, 256]
     tag = "[-Rpass-analysis=kernel-resource-usage]"
-    fn = "x.hip:1:1: remark: Function Name: _ZN7dynamix18stream_pass_kernelILi%dELi0ELi1EEEvNS_10StreamArgsE " + tag
+    fn = "x.hip:1:1: remark: Function Name: _ZN7dynamix18stream_pass_kernelILi%dELi0ELi1ELi0EEEvNS_10StreamArgsE " + tag
 
     def remarks(K, agprs, scratch, spilled=0):
         return "\n".join([fn % K, "x.hip:1:1: remark:     VGPRs: 246 " + tag,
@@ -297,7 +326,7 @@ def test_build_check_of_register_allocation():
         with pytest.raises(RuntimeError):
             Bd._check_resources(bad, "x.hip")
     # a private segment that no vector register was spilled to is reported for a look at the code
-    assert Bd._check_resources(remarks(32, 256, 36), "x.hip") == [(32, 0, 1)]
+    assert Bd._check_resources(remarks(32, 256, 36), "x.hip") == [(32, 0, 1, 0)]
     assert Bd._uses_scratch("\tv_add_f32 v1, v2, v3\n\tscratch_store_dword off, v249, off\n")
     assert not Bd._uses_scratch("\tbuffer_store_dwordx4 v[1:4], v5, s[8:11], 0 offen nt\n"
                                 "\t.amdhsa_private_segment_fixed_size 36\n")
