@@ -52,7 +52,8 @@ typedef enum {
                                  DYNAMIX_STATIC_SCRATCH_BYTES of workspace */
 } dynamix_status;
 
-enum { DYNAMIX_K_MAX = 64 };        /* most workers per call: pointers and weights travel in the kernel arguments */
+enum { DYNAMIX_K_MAX = 256 };       /* most workers per call: pointers and weights travel in the kernel arguments */
+enum { DYNAMIX_K_MAX_ONE_SWEEP = 64 }; /* up to here every gradient byte is read once; above, twice (see below) */
 enum { DYNAMIX_K_MAX_STATEFUL = 24 }; /* most workers for the fused updates that carry optimizer state */
 enum { DYNAMIX_STATIC_SCRATCH_BYTES = 4 << 20 }; /* workspace of dynamix_grad_aggregate_stats_static */
 enum { DYNAMIX_STATS_HEAD = 8 };    /* scalars in front of the per-worker entries of a record */
@@ -86,6 +87,14 @@ enum {
  *                  not.)
  * batch_sizes      HOST array of K per-worker batch sizes b_k, each > 0.
  * K, P             number of workers (1..DYNAMIX_K_MAX) and elements per gradient (>= 1).
+ *                  Up to DYNAMIX_K_MAX_ONE_SWEEP workers the K values of an element stay in
+ *                  registers until its aggregate is known and every gradient byte is read from
+ *                  memory once.  Above, they do not fit: the kernel then sweeps the gradients
+ *                  twice, 32 block iterations at a time (first G and its norm, G parked on chip
+ *                  and written in one burst; then n_k and d_k, sixteen workers at a time), and
+ *                  the memory traffic is 2 K P sizeof(dtype) read + 4 P written.  Same results,
+ *                  same reproducibility; the fused model updates are not available there
+ *                  (DYNAMIX_ERR_ARG).
  * dtype            a dynamix_dtype.
  * segment_offsets  HOST array, or NULL.  NULL: one record for [0, P) only.  Otherwise strictly
  *                  increasing element offsets that start at 0; the array ends at the first

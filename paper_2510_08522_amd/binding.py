@@ -18,7 +18,8 @@ DYNAMIX_ERR_NULL, DYNAMIX_ERR_ARG, DYNAMIX_ERR_SEGMENTS = 1, 2, 3
 DYNAMIX_ERR_ALIGN, DYNAMIX_ERR_NOMEM, DYNAMIX_ERR_HIP = 4, 5, 6
 DYNAMIX_ERR_CAPACITY = 7
 DYNAMIX_STATIC_SCRATCH_BYTES = 4 << 20
-DYNAMIX_K_MAX = 64
+DYNAMIX_K_MAX = 256
+DYNAMIX_K_MAX_ONE_SWEEP = 64
 DYNAMIX_K_MAX_STATEFUL = 24
 DYNAMIX_STATS_HEAD = 8
 STAT = {"agg_sqnorm": 0, "tr_sigma": 1, "agg_sqnorm_unbiased": 2, "noise_scale": 3,

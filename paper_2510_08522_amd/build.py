@@ -34,11 +34,15 @@ def _jobs():
     jobs.append((os.path.join(CSRC, "final_reduce.hip"), os.path.join(OBJ, "final_reduce.o"), []))
     jobs.append((os.path.join(CSRC, "cycle.hip"), os.path.join(OBJ, "cycle.o"), []))
     jobs.append((os.path.join(CSRC, "hbm_probe.hip"), os.path.join(OBJ, "hbm_probe.o"), []))
+    jobs.append((os.path.join(CSRC, "wide_pass.hip"), os.path.join(OBJ, "wide_pass.o"), []))
     jobs.append((os.path.join(CSRC, "api.hip"), os.path.join(OBJ, "api.o"), []))
     return jobs
 
 
 _KERNEL = re.compile(r"stream_pass_kernelILi(\d+)ELi(\d+)ELi(\d+)ELi(\d+)E")
+
+
+_WIDE_KERNEL = re.compile(r"wide_pass_kernelILi(\d+)E")
 
 
 def _bank_registers(K, dtype, U, opt=0):
@@ -69,6 +73,9 @@ def _check_resources(remarks, src):
         if "Function Name:" in line:
             m = _KERNEL.search(line)
             name = tuple(int(x) for x in m.groups()) if m else None
+            w = _WIDE_KERNEL.search(line)
+            if w:   # the two-sweep kernel (K > 64, no banks): named (65, dtype, 1, 0) here
+                name = (65, int(w.group(1)), 1, 0)
         elif name is not None:
             m = re.search(r"remark:\s+(AGPRs|ScratchSize \[bytes/lane\]|VGPRs Spill): (\d+)", line)
             if not m:
@@ -102,7 +109,7 @@ def _uses_scratch(assembly):
 def _compile(job):
     src, obj, defs = job
     cmd = [HIPCC] + FLAGS + defs + ["-c", src, "-o", obj]
-    check = src.endswith("stream_pass_inst.hip")
+    check = src.endswith("stream_pass_inst.hip") or src.endswith("wide_pass.hip")
     if check:
         cmd.append("-Rpass-analysis=kernel-resource-usage")
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -48,12 +48,14 @@ static const Unit* unit_for(int K, int dtype, int opt)
 
 hipError_t launch_stream_pass(int K, int dtype, int opt, int grid, const StreamArgs& a, hipStream_t s)
 {
+    if (K > kKMax && opt == kOptNone) return launch_wide_pass(K, dtype, grid, a, s);
     const Unit* u = unit_for(K, dtype, opt);
     return u ? u->launch(K, grid, a, s) : hipErrorInvalidValue;
 }
 
 int stream_pass_blocks_per_cu(int K, int dtype, int opt)
 {
+    if (K > kKMax && K <= kKWide && opt == kOptNone) return wide_pass_blocks_per_cu(dtype);
     const Unit* u = unit_for(K, dtype, opt);
     return u ? u->occupancy(K) : 0;
 }
@@ -481,7 +483,7 @@ int upload_static(const Plan& pl, hipStream_t stream)
 
 int check_shape(int32_t K, int64_t P, int32_t dtype, const int64_t* offsets, int64_t S)
 {
-    if (K < 1 || K > kKMax || P < 1 || dtype < DYNAMIX_F32 || dtype > DYNAMIX_F16)
+    if (K < 1 || K > kKWide || P < 1 || dtype < DYNAMIX_F32 || dtype > DYNAMIX_F16)
         return DYNAMIX_ERR_ARG;
     if (S < 0 || S > INT32_MAX / 4) return DYNAMIX_ERR_SEGMENTS;
     if ((S == 0) != (offsets == nullptr)) return DYNAMIX_ERR_SEGMENTS;
@@ -525,6 +527,7 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
         (reinterpret_cast<uintptr_t>(up.state2) & 15u))
         return DYNAMIX_ERR_ALIGN;
     if (up.opt != kOptNone && K > kKMaxOpt) return DYNAMIX_ERR_ARG;
+    if (params && K > kKMax) return DYNAMIX_ERR_ARG;   // the two-sweep kernel has no fused update
 
     // ---- weights: B in 64-bit integers, w_k = b_k / B rounded once to fp32
     int64_t B = 0;

@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void cycle_accumulate_kernel(const double* sta
 }
 
 struct CycleArgs {
-    double b[kKMax];
+    double b[kKWide];
     double B, eta, delta;
     const double* window;
     double* summary;
@@ -90,7 +90,7 @@ int dynamix_cycle_summary(const double* window, int32_t K, int64_t num_segments,
         return DYNAMIX_ERR_ALIGN;
     dynamix::CycleArgs a;
     int64_t B = 0;
-    for (int k = 0; k < dynamix::kKMax; ++k) a.b[k] = 0.0;
+    for (int k = 0; k < dynamix::kKWide; ++k) a.b[k] = 0.0;
     for (int k = 0; k < K; ++k) {
         a.b[k] = (double)batch_sizes[k];
         B += batch_sizes[k];

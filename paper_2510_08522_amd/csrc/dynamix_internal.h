@@ -5,7 +5,9 @@
 
 namespace dynamix {
 
-constexpr int kKMax = 64;        // workers per call; pointers and weights travel by value
+constexpr int kKMax = 64;        // most workers of the one-sweep kernels (all K values of a vector in registers)
+constexpr int kKWide = 256;      // most workers per call (two-sweep kernel above kKMax); pointers
+                                 // and weights travel by value in the kernel arguments
 // Threads per block of the streaming pass: four wave64, one per SIMD of the compute unit the
 // block has to itself, so that a wave may use up to 512 registers (four waves read as fast as
 // eight: measured).
@@ -36,10 +38,10 @@ constexpr int unroll_for(int K, int opt = kOptNone)
 // 32-bit words a lane loads at a time: four (128-bit loads) up to 32 workers, two up to 48, one
 // above, so that the K vectors of a lane plus the 2K+1 running sums stay within the 256 vector
 // registers an instruction can address.
-constexpr int load_words_for(int K) { return K > 48 ? 1 : K > 32 ? 2 : 4; }
+constexpr int load_words_for(int K) { return K > kKMax ? 4 : K > 48 ? 1 : K > 32 ? 2 : 4; }
 // Whether the streaming pass for K workers may take its tiles as interleaved 256-byte chunks
 // (see stream_pass.h); the host then starts every block's span at a multiple of 4 KB.
-constexpr bool interleaves(int K) { return load_words_for(K) == 4 && K >= 8; }
+constexpr bool interleaves(int K) { return K >= 8 && K <= 32; }
 // elements per vector
 constexpr int vec_elems(int K, int dtype) { return load_words_for(K) * (dtype == kF32 ? 1 : 2); }
 
@@ -56,8 +58,8 @@ struct Piece {
 };
 
 struct StreamArgs {
-    const void* g[kKMax];        // K device pointers
-    float w[kKMax];              // b_k / B, rounded once to fp32
+    const void* g[kKWide];       // K device pointers
+    float w[kKWide];             // b_k / B, rounded once to fp32
     const Piece* pieces;
     const int32_t* block_range;  // [grid][2] first and one-past-last piece of each block
     float* out_agg;              // may be null
@@ -83,7 +85,7 @@ struct StreamArgs {
 };
 
 struct FinalArgs {
-    double b[kKMax];             // batch sizes
+    double b[kKWide];            // batch sizes
     double B;                    // their sum
     const double* partials;
     const int32_t* rec_range;    // [records][2]: first and one-past-last piece of each record
@@ -101,6 +103,9 @@ hipError_t launch_stream_pass(int K, int dtype, int opt, int grid, const StreamA
 // Resident blocks per compute unit of that kernel (0 on error).
 int stream_pass_blocks_per_cu(int K, int dtype, int opt);
 hipError_t launch_final_reduce(int records, const FinalArgs& a, hipStream_t s);
+// The two-sweep kernel for kKMax < K <= kKWide (aggregate written or statistics only).
+hipError_t launch_wide_pass(int K, int dtype, int grid, const StreamArgs& a, hipStream_t s);
+int wide_pass_blocks_per_cu(int dtype);
 
 // One instantiation unit per update kind, dtype and group of eight K:
 // launch_stream_pass_<opt>_<dtype>_<first K>.

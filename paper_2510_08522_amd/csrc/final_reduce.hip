@@ -63,12 +63,12 @@ __global__ __launch_bounds__(kFinalBlock) void final_reduce_kernel(const FinalAr
         p0 = min(p1, p0 + (int)blockIdx.x * per);
         p1 = min(p1, p0 + per);
     }
-    const int groups = kFinalBlock / W;  // >= 7 because W <= 129
+    const int groups = kFinalBlock / W;  // >= 1 because W <= 513
     // the streaming pass before this kernel has drawn all of its tail pieces
     if (blockIdx.x == 0 && tid == 0) *a.queue = 0;
 
     __shared__ double part[kFinalBlock];
-    __shared__ double tot[2 * kKMax + 1];
+    __shared__ double tot[2 * kKWide + 1];
 
     if (tid < W * groups) {
         const int col = tid % W, grp = tid / W;
@@ -101,11 +101,11 @@ __global__ __launch_bounds__(kFinalBlock) void final_reduce_kernel(const FinalAr
 }
 
 // Record 0 from the sums of its ranges (launched after final_reduce_kernel when slices > 1).
-__global__ __launch_bounds__(2 * kKMax + 1) void final_fold_kernel(const FinalArgs a)
+__global__ __launch_bounds__(2 * kKWide + 1) void final_fold_kernel(const FinalArgs a)
 {
     const int W = 2 * a.K + 1;
     const int tid = threadIdx.x;
-    __shared__ double tot[2 * kKMax + 1];
+    __shared__ double tot[2 * kKWide + 1];
     if (tid < W) {
         double s = 0.0;
         for (int m = 0; m < a.slices; ++m) s += a.slice_sums[m * W + tid];
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(2 * kKMax + 1) void final_fold_kernel(const FinalAr
 hipError_t launch_final_reduce(int records, const FinalArgs& a, hipStream_t s)
 {
     final_reduce_kernel<<<dim3(records + a.slices - 1), dim3(kFinalBlock), 0, s>>>(a);
-    if (a.slices > 1) final_fold_kernel<<<dim3(1), dim3(2 * kKMax + 1), 0, s>>>(a);
+    if (a.slices > 1) final_fold_kernel<<<dim3(1), dim3(2 * kKWide + 1), 0, s>>>(a);
     return hipGetLastError();
 }
 

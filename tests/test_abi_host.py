@@ -61,7 +61,8 @@ def test_header_is_plain_c_and_links_from_a_c_program(tmp_path):
 def test_stats_count_and_status_strings():
     assert D.dynamix_stats_count(4, 0) == 16
     assert D.dynamix_stats_count(32, 148) == 149 * 72
-    assert D.dynamix_stats_count(0, 0) == -1 and D.dynamix_stats_count(65, 0) == -1
+    assert D.dynamix_stats_count(0, 0) == -1 and D.dynamix_stats_count(257, 0) == -1
+    assert D.dynamix_stats_count(256, 1) == 2 * 520
     assert D.dynamix_stats_count(4, -1) == -1
     seen = {D.dynamix_status_string(i) for i in range(8)}
     assert len(seen) == 8 and D.dynamix_status_string(0) == "ok"
@@ -82,7 +83,7 @@ def test_validation_precedes_any_device_work():
     assert raw(ok_p, ok_b, 2, 100, stats=None) == B.DYNAMIX_ERR_NULL
     assert raw([A16, None], ok_b, 2, 100) == B.DYNAMIX_ERR_NULL
     assert raw(ok_p, ok_b, 0, 100) == B.DYNAMIX_ERR_ARG
-    assert raw([A16] * 65, [1] * 65, 65, 100) == B.DYNAMIX_ERR_ARG
+    assert raw([A16] * 257, [1] * 257, 257, 100) == B.DYNAMIX_ERR_ARG
     assert raw(ok_p, ok_b, 2, 0) == B.DYNAMIX_ERR_ARG
     assert raw(ok_p, ok_b, 2, 100, dtype=3) == B.DYNAMIX_ERR_ARG
     assert raw(ok_p, ok_b, 2, 100, dtype=-1) == B.DYNAMIX_ERR_ARG
