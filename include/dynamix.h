@@ -262,6 +262,50 @@ int     dynamix_cycle_summary(const double* window, int32_t K, int64_t num_segme
 int64_t dynamix_cycle_summary_count(int32_t K, int64_t num_segments);
 
 /*
+ * Host side of an adjustment cycle (no device work; every pointer below is a HOST pointer).
+ * Every k iterations the paper's agent maps each worker's state to one of five batch size
+ * adjustments with a policy whose parameters all workers share, pi_theta(a | s_i, s_global)
+ * (Problem Formulation, "Reinforcement learning framework"), the batch size moves by that
+ * amount and is clamped to [x_min, x_max] = [32, 1024] ("Action space and batch size adjustment";
+ * Algorithm 1, the action and batch-size steps), and the reward is
+ *     r = A_mean + alpha max(0, dA) - beta T_iter - delta (log2 b - 5)   [- eta (sigma2_norm + sigma_norm)
+ *                                                                         with adaptive optimizers]
+ * ("Reward function design").  The paper gives neither the network's shape nor any coefficient:
+ * both are arguments.  The network here is a multi-layer perceptron with tanh between layers and
+ * a softmax over the five actions; training it is outside this library.
+ *
+ * dynamix_policy_weight_count: floats a network with num_layers >= 2 layer sizes needs: for each
+ *   pair of consecutive sizes (in, out) a row-major out x in matrix followed by out biases; -1
+ *   for invalid sizes.
+ * dynamix_policy_forward: states is K rows of layer_sizes[0] floats (a worker's local state
+ *   followed by the global state); the last layer size must be DYNAMIX_NUM_ACTIONS; probs
+ *   receives K rows of DYNAMIX_NUM_ACTIONS action probabilities (sums in double, outputs float).
+ * dynamix_policy_choose: actions[k] = index into DYNAMIX_ACTIONS; uniforms == NULL picks the
+ *   most probable action (the first of equals), otherwise uniforms[k] in [0, 1) is the caller's
+ *   random draw and the index is the inverse of the cumulative distribution there (the library
+ *   draws no random numbers itself).
+ * dynamix_batch_sizes_step: next[k] = max(min(b[k] + DYNAMIX_ACTIONS[actions[k]], b_max), b_min).
+ * dynamix_cycle_rewards: the reward above per worker; sigma2_norm and sigma_norm are the cycle
+ *   means from dynamix_cycle_summary (global record, entries DYNAMIX_STAT_SIGMA2_NORM and
+ *   DYNAMIX_STAT_SIGMA_NORM of the means), used only when adaptive_optimizer != 0.
+ * dynamix_discounted_return: sum_t gamma^t rewards[t] over count cycles.
+ * All return a dynamix_status except the two that return a count or a value.
+ */
+enum { DYNAMIX_NUM_ACTIONS = 5 };
+#define DYNAMIX_ACTIONS {-100, -25, 0, 25, 100}
+int64_t dynamix_policy_weight_count(const int32_t* layer_sizes, int32_t num_layers);
+int     dynamix_policy_forward(const float* weights, const int32_t* layer_sizes, int32_t num_layers,
+                               const float* states, int32_t K, float* probs);
+int     dynamix_policy_choose(const float* probs, int32_t K, const float* uniforms, int32_t* actions);
+int     dynamix_batch_sizes_step(const int32_t* batch_sizes, const int32_t* actions, int32_t K,
+                                 int32_t b_min, int32_t b_max, int32_t* next_batch_sizes);
+int     dynamix_cycle_rewards(const double* mean_accuracy, const double* accuracy_gain,
+                              const double* iteration_time, const int32_t* batch_sizes, int32_t K,
+                              double alpha, double beta, double delta, double eta, double sigma2_norm,
+                              double sigma_norm, int32_t adaptive_optimizer, double* rewards);
+double  dynamix_discounted_return(const double* rewards, int64_t count, double gamma);
+
+/*
  * Kernel timing (profiling aid).  dynamix_timing_begin(capacity) creates `capacity` slots of HIP
  * events (capacity 0 switches timing off and frees them).  While slots remain, every call to the
  * aggregate entry points records three events on its stream: before the streaming pass, between

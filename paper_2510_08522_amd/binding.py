@@ -81,6 +81,19 @@ def load():
     lib.dynamix_cycle_summary_count.argtypes = [i32, i64]
     lib.dynamix_hbm_probe.restype = ctypes.c_int
     lib.dynamix_hbm_probe.argtypes = [vp, i32, i64, i32, i32, vp]
+    f64 = ctypes.c_double
+    lib.dynamix_policy_weight_count.restype = i64
+    lib.dynamix_policy_weight_count.argtypes = [vp, i32]
+    lib.dynamix_policy_forward.restype = ctypes.c_int
+    lib.dynamix_policy_forward.argtypes = [vp, vp, i32, vp, i32, vp]
+    lib.dynamix_policy_choose.restype = ctypes.c_int
+    lib.dynamix_policy_choose.argtypes = [vp, i32, vp, vp]
+    lib.dynamix_batch_sizes_step.restype = ctypes.c_int
+    lib.dynamix_batch_sizes_step.argtypes = [vp, vp, i32, i32, i32, vp]
+    lib.dynamix_cycle_rewards.restype = ctypes.c_int
+    lib.dynamix_cycle_rewards.argtypes = [vp, vp, vp, vp, i32, f64, f64, f64, f64, f64, f64, i32, vp]
+    lib.dynamix_discounted_return.restype = f64
+    lib.dynamix_discounted_return.argtypes = [vp, i64, f64]
     lib.dynamix_release_cached.restype = ctypes.c_int
     lib.dynamix_release_cached.argtypes = []
     _lib = lib
@@ -362,3 +375,68 @@ def dynamix_grad_aggregate_stats_adam(grads, batch_sizes, params, exp_avg, exp_a
     if rc != DYNAMIX_OK:
         raise DynamixError(rc)
     return out_stats
+
+
+# ---- host side of an adjustment cycle (numpy arrays in, numpy arrays out; no device work)
+DYNAMIX_NUM_ACTIONS = 5
+DYNAMIX_ACTIONS = (-100, -25, 0, 25, 100)
+
+
+def _np(a, dtype):
+    return np.ascontiguousarray(np.asarray(a, dtype=dtype))
+
+
+def _check(rc):
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+
+
+def dynamix_policy_weight_count(layer_sizes):
+    ls = _np(layer_sizes, np.int32)
+    return int(load().dynamix_policy_weight_count(ls.ctypes.data, len(ls)))
+
+
+def dynamix_policy_forward(weights, layer_sizes, states):
+    """Action probabilities float32[K, 5] of the shared policy for K state rows."""
+    ls, w = _np(layer_sizes, np.int32), _np(weights, np.float32)
+    st = _np(states, np.float32)
+    if st.ndim != 2 or st.shape[1] != ls[0] or w.size != dynamix_policy_weight_count(ls):
+        raise ValueError("states must be [K, layer_sizes[0]] and weights must match the layer sizes")
+    probs = np.empty((st.shape[0], DYNAMIX_NUM_ACTIONS), dtype=np.float32)
+    _check(int(load().dynamix_policy_forward(w.ctypes.data, ls.ctypes.data, len(ls), st.ctypes.data,
+                                             st.shape[0], probs.ctypes.data)))
+    return probs
+
+
+def dynamix_policy_choose(probs, uniforms=None):
+    p = _np(probs, np.float32)
+    u = None if uniforms is None else _np(uniforms, np.float32)
+    out = np.empty(p.shape[0], dtype=np.int32)
+    _check(int(load().dynamix_policy_choose(p.ctypes.data, p.shape[0],
+                                            None if u is None else u.ctypes.data, out.ctypes.data)))
+    return out
+
+
+def dynamix_batch_sizes_step(batch_sizes, actions, b_min=32, b_max=1024):
+    b, a = _np(batch_sizes, np.int32), _np(actions, np.int32)
+    out = np.empty_like(b)
+    _check(int(load().dynamix_batch_sizes_step(b.ctypes.data, a.ctypes.data, len(b), int(b_min),
+                                               int(b_max), out.ctypes.data)))
+    return out
+
+
+def dynamix_cycle_rewards(mean_accuracy, accuracy_gain, iteration_time, batch_sizes, alpha, beta, delta,
+                          eta=0.0, sigma2_norm=0.0, sigma_norm=0.0, adaptive_optimizer=False):
+    A, dA, T = (_np(x, np.float64) for x in (mean_accuracy, accuracy_gain, iteration_time))
+    b = _np(batch_sizes, np.int32)
+    out = np.empty(len(b), dtype=np.float64)
+    _check(int(load().dynamix_cycle_rewards(A.ctypes.data, dA.ctypes.data, T.ctypes.data, b.ctypes.data,
+                                            len(b), float(alpha), float(beta), float(delta), float(eta),
+                                            float(sigma2_norm), float(sigma_norm),
+                                            int(bool(adaptive_optimizer)), out.ctypes.data)))
+    return out
+
+
+def dynamix_discounted_return(rewards, gamma):
+    r = _np(rewards, np.float64)
+    return float(load().dynamix_discounted_return(r.ctypes.data, len(r), float(gamma)))

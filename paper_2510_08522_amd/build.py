@@ -35,6 +35,7 @@ def _jobs():
     jobs.append((os.path.join(CSRC, "cycle.hip"), os.path.join(OBJ, "cycle.o"), []))
     jobs.append((os.path.join(CSRC, "hbm_probe.hip"), os.path.join(OBJ, "hbm_probe.o"), []))
     jobs.append((os.path.join(CSRC, "wide_pass.hip"), os.path.join(OBJ, "wide_pass.o"), []))
+    jobs.append((os.path.join(CSRC, "policy.cpp"), os.path.join(OBJ, "policy.o"), []))
     jobs.append((os.path.join(CSRC, "api.hip"), os.path.join(OBJ, "api.o"), []))
     return jobs
 
