@@ -326,6 +326,8 @@ int     dynamix_timing_read(int32_t index, float* stream_pass_ms, float* final_r
  * `bytes` each (a multiple of 4096 is used).  Modes:
  *   DYNAMIX_PROBE_READ         read `count` (1, 2, 4, 8, 16 or 32) buffers, 4 KB tiles in order
  *   DYNAMIX_PROBE_READ_SPREAD  the same in the interleaved 256-byte chunks of the streaming pass
+ *   DYNAMIX_PROBE_READ_SPREAD_128B, _512B  the same with chunks of 128 and 512 bytes (32 and 8
+ *                              units of 4 KB per load instruction of a block instead of 16)
  *   DYNAMIX_PROBE_WRITE        count == 1: write buffers[0]
  *   DYNAMIX_PROBE_COPY         count == 2: buffers[1] := buffers[0]
  * Every probe kernel reserves more than half of a compute unit's LDS, so two probes launched
@@ -333,7 +335,7 @@ int     dynamix_timing_read(int32_t index, float* stream_pass_ms, float* final_r
  * how reading beside writing is measured.  Only enqueues one kernel on `stream`; validates first.
  */
 enum { DYNAMIX_PROBE_READ = 0, DYNAMIX_PROBE_READ_SPREAD = 1, DYNAMIX_PROBE_WRITE = 2,
-       DYNAMIX_PROBE_COPY = 3 };
+       DYNAMIX_PROBE_COPY = 3, DYNAMIX_PROBE_READ_SPREAD_128B = 4, DYNAMIX_PROBE_READ_SPREAD_512B = 5 };
 int dynamix_hbm_probe(const void* const* buffers, int32_t count, int64_t bytes, int32_t mode,
                       int32_t blocks, void* stream);
 

@@ -113,6 +113,7 @@ def dynamix_release_cached():
 
 
 DYNAMIX_PROBE_READ, DYNAMIX_PROBE_READ_SPREAD, DYNAMIX_PROBE_WRITE, DYNAMIX_PROBE_COPY = 0, 1, 2, 3
+DYNAMIX_PROBE_READ_SPREAD_128B, DYNAMIX_PROBE_READ_SPREAD_512B = 4, 5
 
 
 def dynamix_hbm_probe(buffers, nbytes, mode, blocks, stream=None):

@@ -23,7 +23,7 @@ struct ProbeArgs {
     const char* src[32];
     char* dst;
     int64_t vectors;   // 16-byte vectors per buffer
-    int32_t spread;    // read 256-byte chunks of sixteen 4 KB units per load instruction
+    int32_t spread;    // 0: consecutive 4 KB tiles; L = 8, 16, 32: chunks of L vectors, see below
     float* sink;       // never written: keeps the loads alive
 };
 
@@ -34,8 +34,9 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc(const void* base, int64_t
 }
 
 // Block b owns the contiguous span of tiles [b * per, (b + 1) * per) of every stream; a tile is
-// 256 vectors (4 KB) per stream.  With `spread`, sixteen tiles form a group and load i of a group
-// takes chunk (i + unit) mod 16 of each of its sixteen 4 KB units, as the streaming pass does.
+// 256 vectors (4 KB) per stream.  With spread = L, G = 256 / L tiles form a group and load i of a
+// group takes, from each of the group's G units of 4 KB, the chunk of L vectors number
+// (i + unit) mod G: L = 16 (256-byte chunks of sixteen units) is what the streaming pass does.
 template <int NS>
 __global__ __launch_bounds__(kProbeBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) void probe_read_kernel(
     const ProbeArgs a)
@@ -43,18 +44,20 @@ __global__ __launch_bounds__(kProbeBlock) __attribute__((amdgpu_waves_per_eu(1, 
     __shared__ char reserve[kReserveLds];
     const int tid = threadIdx.x;
     const int64_t tiles = a.vectors / kProbeBlock;          // whole tiles only
-    const int64_t per = (tiles + gridDim.x - 1) / gridDim.x / 16 * 16 + 16;   // whole groups
+    const int L = a.spread ? a.spread : 16;      // vectors per chunk
+    const int G = kProbeBlock / L;               // tiles per group = units per group = chunks per unit
+    const int64_t per = (tiles + gridDim.x - 1) / gridDim.x / G * G + G;   // whole groups
     const int64_t t0 = (int64_t)blockIdx.x * per;
     const int64_t t1 = t0 + per < tiles ? t0 + per : tiles;
     float acc = 0.f;
-    const int unit = tid >> 4;
+    const int unit = tid / L;
     for (int64_t t = t0; t < t1; ++t) {
         u32x4 x[NS];
-        const int64_t group = t & ~(int64_t)15;
-        const bool whole = group + 16 <= t1;
-        const int i = (int)(t & 15);
-        const int group_tiles = (int)(tiles - group < 16 ? tiles - group : 16);   // inside the buffer
-        const int lane_vec = a.spread && whole ? ((unit << 4) + ((i + unit) & 15)) * 16 + (tid & 15)
+        const int64_t group = t / G * G;
+        const bool whole = group + G <= t1;
+        const int i = (int)(t - group);
+        const int group_tiles = (int)(tiles - group < G ? tiles - group : G);   // inside the buffer
+        const int lane_vec = a.spread && whole ? (unit * G + (i + unit) % G) * L + tid % L
                                                : i * kProbeBlock + tid;
 #pragma unroll
         for (int k = 0; k < NS; ++k)
@@ -149,7 +152,10 @@ extern "C" int dynamix_hbm_probe(const void* const* buffers, int32_t count, int6
     switch (mode) {
     case DYNAMIX_PROBE_READ:
     case DYNAMIX_PROBE_READ_SPREAD:
-        a.spread = mode == DYNAMIX_PROBE_READ_SPREAD;
+    case DYNAMIX_PROBE_READ_SPREAD_128B:
+    case DYNAMIX_PROBE_READ_SPREAD_512B:
+        a.spread = mode == DYNAMIX_PROBE_READ ? 0 : mode == DYNAMIX_PROBE_READ_SPREAD ? 16
+                 : mode == DYNAMIX_PROBE_READ_SPREAD_128B ? 8 : 32;
         a.sink = static_cast<float*>(const_cast<void*>(buffers[0]));   // (never written)
         switch (count) {
         case 1: probe_read_kernel<1><<<grid, block, 0, s>>>(a); break;

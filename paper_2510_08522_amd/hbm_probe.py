@@ -67,7 +67,10 @@ def main(argv=None):
         B.dynamix_hbm_probe(bufs, nbytes, B.DYNAMIX_PROBE_READ_SPREAD, units)
         torch.cuda.synchronize()
 
-    for name, mode in (("read_consecutive", B.DYNAMIX_PROBE_READ), ("read_interleaved", B.DYNAMIX_PROBE_READ_SPREAD)):
+    for name, mode in (("read_consecutive", B.DYNAMIX_PROBE_READ),
+                       ("read_interleaved", B.DYNAMIX_PROBE_READ_SPREAD),
+                       ("read_interl_128B", B.DYNAMIX_PROBE_READ_SPREAD_128B),
+                       ("read_interl_512B", B.DYNAMIX_PROBE_READ_SPREAD_512B)):
         ms = _time(lambda: B.dynamix_hbm_probe(bufs, nbytes, mode, units), args.reps)
         res[name] = {"ms": ms, "GBps": K * nbytes / ms / 1e6}
         say("%-18s %d x %.1f MB: %.4f ms  %.0f GB/s" % (name, K, nbytes / 1e6, ms, K * nbytes / ms / 1e6))

@@ -28,7 +28,8 @@ def test_probe_copy_copies_and_write_writes():
                        .repeat_interleave(256))
     print("case probe read", flush=True)
     before = src.clone()
-    for mode in (B.DYNAMIX_PROBE_READ, B.DYNAMIX_PROBE_READ_SPREAD):
+    for mode in (B.DYNAMIX_PROBE_READ, B.DYNAMIX_PROBE_READ_SPREAD, B.DYNAMIX_PROBE_READ_SPREAD_128B,
+                 B.DYNAMIX_PROBE_READ_SPREAD_512B):
         for k in (1, 2, 4, 8, 16, 32):
             B.dynamix_hbm_probe([src] * k, n, mode, 3)
     torch.cuda.synchronize()
