@@ -54,7 +54,7 @@ typedef enum {
 
 enum { DYNAMIX_K_MAX = 256 };       /* most workers per call: pointers and weights travel in the kernel arguments */
 enum { DYNAMIX_K_MAX_ONE_SWEEP = 64 }; /* up to here every gradient byte is read once; above, twice (see below) */
-enum { DYNAMIX_K_MAX_STATEFUL = 24 }; /* most workers for the fused updates that carry optimizer state */
+enum { DYNAMIX_K_MAX_STATEFUL = 32 }; /* most workers for the fused updates that carry optimizer state */
 enum { DYNAMIX_STATIC_SCRATCH_BYTES = 4 << 20 }; /* workspace of dynamix_grad_aggregate_stats_static */
 enum { DYNAMIX_STATS_HEAD = 8 };    /* scalars in front of the per-worker entries of a record */
 

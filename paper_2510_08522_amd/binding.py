@@ -20,7 +20,7 @@ DYNAMIX_ERR_CAPACITY = 7
 DYNAMIX_STATIC_SCRATCH_BYTES = 4 << 20
 DYNAMIX_K_MAX = 256
 DYNAMIX_K_MAX_ONE_SWEEP = 64
-DYNAMIX_K_MAX_STATEFUL = 24
+DYNAMIX_K_MAX_STATEFUL = 32
 DYNAMIX_STATS_HEAD = 8
 STAT = {"agg_sqnorm": 0, "tr_sigma": 1, "agg_sqnorm_unbiased": 2, "noise_scale": 3,
         "noise_scale_biased": 4, "sigma2_norm": 5, "sigma_norm": 6, "count": 7}

@@ -1,8 +1,8 @@
 """Builds libdynamix.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree.
 
 The streaming pass is instantiated for every K in 1..64 and the three storage types, and again
-for K in 1..24 with each of the two optimizer updates that carry state; the instantiations are
-split over 42 translation units of eight kernels that compile in parallel.
+for K in 1..32 with each of the two optimizer updates that carry state; the instantiations are
+split over 48 translation units of eight kernels that compile in parallel.
 Run as `python -m paper_2510_08522_amd.build`.
 """
 import os
@@ -26,7 +26,7 @@ def _jobs():
     jobs = []
     for opt in (0, 1, 2):
         for dt in (0, 1, 2):
-            for lo in range(1, 65 if opt == 0 else 25, 8):
+            for lo in range(1, 65 if opt == 0 else 33, 8):
                 jobs.append((os.path.join(CSRC, "stream_pass_inst.hip"),
                              os.path.join(OBJ, "stream_pass_%d_%d_%d.o" % (opt, dt, lo)),
                              ["-DDYNAMIX_INST_OPT=%d" % opt, "-DDYNAMIX_INST_DT=%d" % dt,
@@ -51,7 +51,7 @@ def _bank_registers(K, dtype, U, opt=0):
     same arithmetic as Shape<> in csrc/stream_pass.h."""
     if K > 44:
         return 0
-    LW, kBlock, stage = (4 if K <= 32 else 2), 256, 152 * 1024
+    LW, kBlock, stage = (4 if K <= (32 if opt == 0 else 24) else 2), 256, 152 * 1024
     Q = (1 if dtype == 0 else 2)
     slots = stage // (kBlock * LW * 4)
     per_tile_slots = U * Q * (1 + opt)          # a parked tile holds one vector per output stream

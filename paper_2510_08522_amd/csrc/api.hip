@@ -145,14 +145,14 @@ struct Layout {
 void make_layout(int K, int dtype, int opt, int64_t P, int S, const int64_t* offsets, int64_t max_grid,
                  Layout& L)
 {
-    const int VEC = vec_elems(K, dtype);
+    const int VEC = vec_elems(K, dtype, opt);
     const int64_t tile = (int64_t)kBlock * unroll_for(K, opt);  // vectors per block iteration
     const int64_t nvec = ceil_div(P, VEC);
     // Spans start at multiples of a wave's worth of vectors (1 KB of every stream), so that the
     // 64 lanes of a wave stay on whole cache lines; a block's last tile may be partial.  Kernels
     // that interleave chunks of 4 KB units start their groups at multiples of 256 vectors, so
     // their spans start there (otherwise every block would begin with a short tile).
-    const int64_t gran = interleaves(K) ? 256 : 64;
+    const int64_t gran = interleaves(K, opt) ? 256 : 64;
     if (max_grid < 1) max_grid = 1;
     L.grid = (int)std::min<int64_t>(std::min(max_grid, ceil_div(nvec, gran)),
                                     std::max<int64_t>(1, nvec / 512));

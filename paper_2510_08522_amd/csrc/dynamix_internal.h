@@ -23,7 +23,8 @@ constexpr int kDtypes = 3;
 // writes 1 + (number of state vectors) streams and reads them first.
 enum : int { kOptNone = 0, kOptMomentum = 1, kOptAdam = 2 };
 constexpr int kOpts = 3;
-constexpr int kKMaxOpt = 24;     // most workers for the updates with state (register budget)
+constexpr int kKMaxOpt = 32;     // most workers for the updates with state (register budget)
+constexpr int kKWideLoadsOpt = 24;   // ... with 16-byte loads; above, they take 8-byte loads
 constexpr int out_streams(int opt) { return 1 + opt; }
 
 // Vectors (16-byte loads) per thread and block iteration.  Small K gets several so that each
@@ -38,12 +39,21 @@ constexpr int unroll_for(int K, int opt = kOptNone)
 // 32-bit words a lane loads at a time: four (128-bit loads) up to 32 workers, two up to 48, one
 // above, so that the K vectors of a lane plus the 2K+1 running sums stay within the 256 vector
 // registers an instruction can address.
-constexpr int load_words_for(int K) { return K > kKMax ? 4 : K > 48 ? 1 : K > 32 ? 2 : 4; }
+constexpr int load_words_for(int K, int opt = kOptNone)
+{
+    return opt != kOptNone && K > kKWideLoadsOpt ? 2 : K > kKMax ? 4 : K > 48 ? 1 : K > 32 ? 2 : 4;
+}
 // Whether the streaming pass for K workers may take its tiles as interleaved 256-byte chunks
 // (see stream_pass.h); the host then starts every block's span at a multiple of 4 KB.
-constexpr bool interleaves(int K) { return K >= 8 && K <= 32; }
+constexpr bool interleaves(int K, int opt = kOptNone)
+{
+    return K >= 8 && K <= 32 && load_words_for(K, opt) == 4;
+}
 // elements per vector
-constexpr int vec_elems(int K, int dtype) { return load_words_for(K) * (dtype == kF32 ? 1 : 2); }
+constexpr int vec_elems(int K, int dtype, int opt = kOptNone)
+{
+    return load_words_for(K, opt) * (dtype == kF32 ? 1 : 2);
+}
 
 // One unit of streaming work: vectors v_begin, v_begin + v_step, ... below v_end are the
 // starts of the block iterations; elements outside [e_lo, e_hi) are masked (segment edges and
@@ -114,7 +124,7 @@ int wide_pass_blocks_per_cu(int dtype);
     int occupancy_stream_pass_##OPT##_##DT##_##LO(int K);
 #define DYNAMIX_FOR_EACH_PLAIN_UNIT(X, DT) \
     X(0, DT, 1) X(0, DT, 9) X(0, DT, 17) X(0, DT, 25) X(0, DT, 33) X(0, DT, 41) X(0, DT, 49) X(0, DT, 57)
-#define DYNAMIX_FOR_EACH_STATE_UNIT(X, OPT, DT) X(OPT, DT, 1) X(OPT, DT, 9) X(OPT, DT, 17)
+#define DYNAMIX_FOR_EACH_STATE_UNIT(X, OPT, DT) X(OPT, DT, 1) X(OPT, DT, 9) X(OPT, DT, 17) X(OPT, DT, 25)
 DYNAMIX_FOR_EACH_PLAIN_UNIT(DYNAMIX_DECLARE_UNIT, 0)
 DYNAMIX_FOR_EACH_PLAIN_UNIT(DYNAMIX_DECLARE_UNIT, 1)
 DYNAMIX_FOR_EACH_PLAIN_UNIT(DYNAMIX_DECLARE_UNIT, 2)

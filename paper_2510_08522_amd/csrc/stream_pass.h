@@ -173,11 +173,12 @@ __device__ __forceinline__ uint32_t from_acc(uint32_t a)
 // bytes added for the second half of a vector.
 constexpr int kMaskedStore = 0x7fff0000;
 
-template <int K, int DT, int U, int NO>
+template <int K, int DT, int U, int OPT>
 struct Shape {
-    static constexpr int kLW = load_words_for(K);                  // words per lane and load
+    static constexpr int NO = out_streams(OPT);
+    static constexpr int kLW = load_words_for(K, OPT);             // words per lane and load
     static constexpr int kVB = kLW * 4;                            // bytes per lane and load
-    static constexpr int kVec = vec_elems(K, DT);                  // elements per vector
+    static constexpr int kVec = vec_elems(K, DT, OPT);             // elements per vector
     static constexpr int kSize = DT == kF32 ? 4 : 2;               // bytes per element
     static constexpr int kQ = kVec / kLW;                          // LW-word pieces of G per vector
     static constexpr int kSlots = kStageBytes / (kBlock * kVB);    // LW-word slots per thread
@@ -193,7 +194,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
     const StreamArgs a)
 {
     constexpr int NO = out_streams(OPT);   // streams written (and, but for the plain aggregate, read first)
-    typedef Shape<K, DT, U, NO> Sh;
+    typedef Shape<K, DT, U, OPT> Sh;
     typedef Words<Sh::kLW> Wd;
     typedef typename Wd::type wvec;
     constexpr int LW = Sh::kLW, VB = Sh::kVB, VEC = Sh::kVec, Q = Sh::kQ, NB = Sh::kTiles;
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
         // arguments again for every tile (scalar loads that hit the scalar cache, at an offset the
         // compiler cannot see through): kept in scalar registers for the whole loop they push so
         // many other scalars into spill lanes of vector registers that the loop runs out of those.
-        constexpr bool kReloadWeights = K >= 31 && K <= 32 && DT == kF32;
+        constexpr bool kReloadWeights = K >= 31 && K <= 32 && DT == kF32 && OPT == kOptNone;
         auto pass1 = [&](const wvec (&xu)[K], float (&Gu)[VEC], const float* kw) {
 #pragma unroll
             for (int c = 0; c < VEC; ++c) Gu[c] = 0.f;
@@ -457,7 +458,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(1, 1))) 
             // taken in consecutive tiles.  The aggregate is written in the same chunks, which
             // costs more than it gains where the write is a large part of the traffic: below
             // eight workers the tiles stay consecutive (measured: 2 to 4 % slower otherwise).
-            constexpr bool kSpread = interleaves(K);
+            constexpr bool kSpread = interleaves(K, OPT);
             // The chunks only pay when they are whole cache lines, so the groups start at a
             // multiple of 256 vectors (the caller says whether the buffers themselves are aligned;
             // a.spread is zero otherwise, and everything is taken in consecutive tiles); the

@@ -312,7 +312,8 @@ def test_build_check_of_register_allocation():
              (64, 1, 1)]] == [256, 256, 256, 256, 256, 256, 256, 0, 0]
     # the updates with state park two or three streams per tile
     assert [Bd._bank_registers(K, d, U, o) for K, d, U, o in
-            [(24, 0, 1, 2), (24, 1, 1, 2), (2, 1, 4, 2), (8, 1, 2, 2), (8, 0, 2, 1)]] == [252, 240, 192, 240, 256]
+            [(24, 0, 1, 2), (24, 1, 1, 2), (2, 1, 4, 2), (8, 1, 2, 2), (8, 0, 2, 1), (32, 0, 1, 2),
+             (32, 1, 1, 1)]] == [252, 240, 192, 240, 256, 252, 256]
     tag = "[-Rpass-analysis=kernel-resource-usage]"
     fn = "x.hip:1:1: remark: Function Name: _ZN7dynamix18stream_pass_kernelILi%dELi0ELi1ELi0EEEvNS_10StreamArgsE " + tag
 

@@ -26,6 +26,8 @@ def kernel_shape(K, dtype, opt=0):
     derives them from K, the storage type and the number of optimizer state vectors it carries:
     (tile elements, LDS tiles, second-bank tiles, tiles per flush cycle)."""
     lw = 4 if K <= 32 else 2 if K <= 48 else 1          # 32-bit words per lane and load
+    if opt and K > 24:
+        lw = 2                                            # the updates with state: 8-byte loads
     q = 1 if dtype == torch.float32 else 2               # stores per vector of the aggregate
     if opt == 0:
         u = 8 if K <= 2 else 4 if K <= 8 else 2 if K <= 16 else 1

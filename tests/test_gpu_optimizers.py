@@ -64,7 +64,7 @@ def adam_case(oracle_mod, w, lr, b1, b2, eps, wd, decoupled, steps, where, agg=N
 
 CASES = [(1, torch.float32), (2, torch.bfloat16), (3, torch.float16), (8, torch.float32),
          (9, torch.bfloat16), (16, torch.float32), (17, torch.float16), (24, torch.float32),
-         (24, torch.bfloat16)]
+         (24, torch.bfloat16), (25, torch.float32), (32, torch.float32), (32, torch.bfloat16)]
 
 
 @pytest.mark.parametrize("K,dtype", CASES)
@@ -93,7 +93,8 @@ def test_stateful_updates_with_segments_and_shared_tail(oracle_mod, monkeypatch)
     monkeypatch.setenv("DYNAMIX_MAX_BLOCKS", "8")
     monkeypatch.setenv("DYNAMIX_TAIL_PERMILLE", "250")
     rng = np.random.default_rng(12)
-    for K, dtype, tile in [(24, torch.float32, 1024), (8, torch.bfloat16, 256 * 2 * 8)]:
+    for K, dtype, tile in [(24, torch.float32, 1024), (8, torch.bfloat16, 256 * 2 * 8),
+                           (32, torch.float32, 512)]:
         P = (8 * 40 + 2) * tile - 3
         cuts = sorted({int(c) for c in rng.integers(1, P, size=5)} | {P - 3 * tile - 7, P - 9})
         off = [0] + cuts + [P]
