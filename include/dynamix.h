@@ -175,7 +175,8 @@ int dynamix_grad_aggregate_stats_sgd(const void* const* grads, const int32_t* ba
  * rewritten in place like params, so neither G nor the state makes an extra round trip through
  * HBM.  params and every state vector: DEVICE, P floats, 16-byte aligned, not overlapping each
  * other or any gradient buffer.  K <= DYNAMIX_K_MAX_STATEFUL (above, the K gradient vectors of a
- * lane and the state leave no registers; DYNAMIX_ERR_ARG).  Statistics, segments, stream,
+ * lane and the state leave no registers; DYNAMIX_ERR_ARG; from 25 workers on the kernels load 8
+ * bytes per lane instead of 16, which costs some read bandwidth).  Statistics, segments, stream,
  * validation and error behaviour as for dynamix_grad_aggregate_stats_ex; the statistics are those
  * of the gradients (these kernels take fewer vectors per block iteration, so the partial sums are
  * added in another order than in the plain call).  All arithmetic of the updates is fp32 (fused multiply-adds,
