@@ -84,6 +84,55 @@ def cpu_baseline(w, sample_elems, threads):
                                         % (n1, dt1)}}
 
 
+def memory_ceiling(D, torch, sets, w, stream):
+    """What the memory system gives plain streaming kernels of the streaming pass's launch shape on
+    this workload's own buffers, measured after the timed region (dynamix_hbm_probe: no
+    arithmetic): the K buffers read and nothing written, the aggregate's bytes written and nothing
+    read.  Their sum is the time of a pass that lost nothing where reads and writes meet."""
+    B = D.binding
+    if w.K not in (1, 2, 4, 8, 16, 32):
+        return None
+    if any(g.data_ptr() % 256 for s in sets for g in s[0]) or any(s[1].data_ptr() % 256 for s in sets):
+        return None
+    units = torch.cuda.get_device_properties(0).multi_processor_count
+    if w.P * w.itemsize < 64 * 4096 * units:     # under 64 tiles per block the probe is not at speed
+        return None
+    in_bytes = w.P * w.itemsize // 4096 * 4096
+    out_bytes = w.P * 4 // 4096 * 4096
+    reps = max(10, min(200, int(2e10 // max(w.bytes_read, 1))))
+    n = [0]
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def read():
+        grads = sets[n[0] % len(sets)][0]
+        n[0] += 1
+        B.dynamix_hbm_probe(grads, in_bytes, B.DYNAMIX_PROBE_READ_SPREAD, units, stream=stream)
+
+    def write():
+        agg = sets[n[0] % len(sets)][1]
+        n[0] += 1
+        B.dynamix_hbm_probe([agg], out_bytes, B.DYNAMIX_PROBE_WRITE, units, stream=stream)
+
+    r_ms, w_ms = timed(read), timed(write)
+    return {"read_only_ms": round(r_ms, 5), "read_only_GBps": round(w.K * in_bytes / r_ms / 1e6, 1),
+            "write_only_ms": round(w_ms, 5), "write_only_GBps": round(out_bytes / w_ms / 1e6, 1),
+            "read_then_write_ms": round(r_ms + w_ms, 5),
+            "read_then_write_GBps_of_read_bytes": round(w.bytes_read / (r_ms + w_ms) / 1e6, 1),
+            "note": "plain streaming kernels (no arithmetic) on the same buffers; the last two "
+                    "figures assume no cost where reads and writes meet"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -247,6 +296,9 @@ def main():
     line["stats_only"] = {"kernel_ms": round(so_ms, 5),
                           "read_GBps": round(read_bytes / so_ms / 1e6, 2),
                           "frac_of_peak": round(read_bytes / so_ms / 1e6 / HBM_PEAK_GBPS, 4)}
+    ceiling = memory_ceiling(D, torch, sets, w, stream)
+    if ceiling:
+        line["memory_ceiling"] = ceiling
     if args.cpu_sample > 0:
         line["cpu_baseline"] = cpu_baseline(w, args.cpu_sample, args.cpu_threads)
     print(json.dumps(line), flush=True)
