@@ -109,7 +109,12 @@ enum {
  * HIP call; on any error nothing is enqueued and a dynamix_status other than DYNAMIX_OK is
  * returned.  Results are valid once the caller has synchronised `stream`.  The first call with
  * a shape on a stream also allocates and uploads the plan; every later one only launches
- * kernels, so it may be recorded into a HIP graph.  Non-finite inputs
+ * kernels.  A call may be recorded into a HIP graph (stream capture): it then carries the upload
+ * of its tables with it, as a few small kernels, so the graph is complete in itself.  The
+ * allocation of a first call is not graph material: make one call with the shape before the
+ * capture, or use dynamix_grad_aggregate_stats_static.  A recorded call refers to the library's
+ * workspace for its shape: dynamix_release_cached(), or 128 other shapes used since, free it, and
+ * a graph that holds such a call must not be replayed afterwards.  Non-finite inputs
  * propagate by IEEE rules.  The library keeps a small workspace per (device, stream, shape),
  * allocated on the first call with that shape and reused afterwards; two calls that share it
  * must be ordered on that stream.  For fixed inputs, shape and device the results are bitwise
@@ -143,7 +148,10 @@ int dynamix_grad_aggregate_stats_ex(const void* const* grads, const int32_t* bat
  * All calls on one GPU share the one array, which keeps the tables of the last shape (a call
  * with the same shape as the one before only launches the two kernels; another shape is uploaded
  * in place): calls on the same GPU must not overlap, whatever their streams; the caller orders
- * them (one stream, or events).  The caller still owns inputs and outputs.
+ * them (one stream, or events).  That holds for replays of a graph the call was recorded into as
+ * well; a recorded call uploads its tables at every replay, and from the first recording on
+ * every call on that GPU does (the host can no longer know what a replay left in the array).
+ * The caller still owns inputs and outputs.
  */
 int dynamix_grad_aggregate_stats_static(const void* const* grads, const int32_t* batch_sizes,
                                         int32_t K, int64_t P, int32_t dtype,

@@ -422,6 +422,10 @@ constexpr int kMaxDevices = 64;
 struct StaticDevice {
     char* ptr = nullptr;            // this device's copy of the scratch array
     std::unique_ptr<Plan> plan;     // the shape whose tables are resident (host side: layout only)
+    // A call recorded into a graph uploads its tables whenever the graph is replayed, behind the
+    // host's back: once that has happened on a device, no call can trust what is resident any
+    // more, and every call uploads its own tables.
+    bool recorded_into_a_graph = false;
 };
 StaticDevice g_static[kMaxDevices];
 
@@ -468,8 +472,9 @@ int get_static_plan(int device, hipStream_t stream, int K, int dtype, int64_t P,
     return DYNAMIX_OK;
 }
 
-// Writes the plan's tables (with a zero tail counter) into the scratch array, on `stream`.
-int upload_static(const Plan& pl, hipStream_t stream)
+// Writes the plan's tables (with a zero tail counter) to its device memory with kernels on
+// `stream` (the static path, and any call that is being recorded into a graph).
+int upload_by_kernels(const Plan& pl, hipStream_t stream)
 {
     PokeArgs pa;
     for (size_t off = 0; off < pl.table_bytes; off += sizeof pa.words) {
@@ -542,9 +547,20 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     const int rc = use_static ? get_static_plan(device, stream, K, dtype, P, (int)S, offsets, &pl)
                               : get_plan(device, stream, K, dtype, up.opt, P, (int)S, offsets, &pl);
     if (rc != DYNAMIX_OK) return rc;
-    if (!pl->uploaded) {
-        if (use_static) {
-            if (upload_static(*pl, stream) != DYNAMIX_OK) return DYNAMIX_ERR_HIP;
+    // A call that is being recorded into a graph executes nothing now: it must carry the upload
+    // of its tables with it (as kernels: a copy from pageable host memory is no graph material),
+    // and it may not change what the host believes to be on the device.
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (stream != nullptr && hipStreamIsCapturing(stream, &capture) != hipSuccess) {
+        (void)hipGetLastError();
+        capture = hipStreamCaptureStatusNone;
+    }
+    const bool recording = capture != hipStreamCaptureStatusNone;
+    const bool was_uploaded = pl->uploaded;
+    if (use_static && recording) g_static[device].recorded_into_a_graph = true;
+    if (!pl->uploaded || recording || (use_static && g_static[device].recorded_into_a_graph)) {
+        if (use_static || recording) {
+            if (upload_by_kernels(*pl, stream) != DYNAMIX_OK) return DYNAMIX_ERR_HIP;
         } else if (hipMemcpyAsync(pl->blob, pl->host.data(), pl->table_bytes,
                                   hipMemcpyHostToDevice, stream) != hipSuccess) {
             return DYNAMIX_ERR_HIP;
@@ -602,7 +618,7 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     pl->uploaded = false;
     if (ev && hipEventRecord(ev[1], stream) != hipSuccess) return DYNAMIX_ERR_HIP;
     if (launch_final_reduce(pl->records, fa, stream) != hipSuccess) return DYNAMIX_ERR_HIP;
-    pl->uploaded = true;
+    pl->uploaded = recording ? was_uploaded : true;
     if (ev && hipEventRecord(ev[2], stream) != hipSuccess) return DYNAMIX_ERR_HIP;
     return DYNAMIX_OK;
 }

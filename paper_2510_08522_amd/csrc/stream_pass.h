@@ -4,7 +4,10 @@
 // Per 16-byte vector a lane loads the K workers' values, forms the weighted aggregate
 // G = sum_k w_k g_k in a fixed k order, and then, while the K values are still in registers,
 // adds g^2 to the worker's squared norm, (g - G)^2 to its squared deviation and G^2 to the
-// aggregate's squared norm.  Nothing is read twice and the only write is G.  The kernel is
+// aggregate's squared norm.  Nothing is read twice and the only write is G, or, with a model
+// update fused in (template parameter OPT), the parameters and the optimizer's state vectors,
+// which then travel through the pass as further streams: read a tile ahead like the gradients,
+// rewritten in place through the same staging as G.  The kernel is
 // bound by HBM bandwidth (about one flop per byte), so there is no LDS tiling of the data and no
 // MFMA: the work is coalesced 128-bit loads, fp32 FMAs and one block reduction per piece.
 #pragma once

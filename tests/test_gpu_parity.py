@@ -463,6 +463,33 @@ def test_steady_state_call_can_be_captured_in_a_graph(oracle_mod, monkeypatch):
     compare(a_graph, s_graph, ragg, rst, w.batch_sizes, where="graph replay")
 
 
+def test_recorded_call_carries_its_table_upload(oracle_mod):
+    """A call recorded into a graph right after its plan was built, before any eager call has put
+    the tables on the device for good: the replays must not depend on what ran eagerly."""
+    w = W.config("C2", device=DEV, P=777_001)
+    out_agg = torch.empty(w.P, dtype=torch.float32, device=DEV)
+    out_st = torch.empty((1, HEAD + 2 * w.K), dtype=torch.float64, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    # the plan of a stream is built by the first call on it; the capture mode that tolerates the
+    # allocation lets that first call be the recorded one
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side, capture_error_mode="relaxed"):
+        D.dynamix_grad_aggregate_stats_ex(w.grads, w.batch_sizes, out_agg=out_agg,
+                                          out_stats=out_st, stream=torch.cuda.current_stream())
+    ragg, rst = run_oracle(oracle_mod, w)
+    for rep in range(3):
+        out_agg.zero_()
+        out_st.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        compare(out_agg.cpu().numpy(), out_st.cpu().numpy(), ragg, rst, w.batch_sizes,
+                where="recorded first call, replay %d" % rep)
+        a_eager, s_eager = run_gpu(w)
+        assert np.array_equal(out_agg.cpu().numpy(), a_eager) and np.array_equal(out_st.cpu().numpy(), s_eager)
+
+
 def test_more_than_two_to_the_31_elements(oracle_mod):
     # indices beyond 32 bits: two workers, 2^31 + 4099 fp32 elements each (8.6 GB per buffer)
     P = (1 << 31) + 4099

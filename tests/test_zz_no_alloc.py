@@ -97,3 +97,43 @@ def test_static_entry_rejects_what_does_not_fit():
                                       out_stats=st)
     small = W.config("C1", device=DEV, P=50_001)
     same(both(small))
+
+
+def test_static_entry_recorded_into_a_graph_without_a_call_before(oracle_mod):
+    """The use the entry point is for: the very first call with a shape is made under stream
+    capture, in the capture mode that rejects allocations.  Replays are interleaved with eager
+    calls of another shape, which overwrite the tables in the static array in between; every
+    replay and every eager call must still give the allocating entry point's bits."""
+    wa = W.make(12, 900_001, torch.float32, np.arange(12) * 7 + 16, 1e-3, 1e-2, seed=90, device=DEV,
+                one_allocation=False)
+    wb = W.config("C1", device=DEV, P=333_337)
+    ref_a = D.dynamix_grad_aggregate_stats_ex(wa.grads, wa.batch_sizes)
+    ref_b = D.dynamix_grad_aggregate_stats_ex(wb.grads, wb.batch_sizes)
+    torch.cuda.synchronize()
+    agg_a = torch.empty(wa.P, dtype=torch.float32, device=DEV)
+    st_a = torch.empty((1, D.DYNAMIX_STATS_HEAD + 2 * wa.K), dtype=torch.float64, device=DEV)
+    agg_b, st_b = torch.empty_like(ref_b[0]), torch.empty_like(ref_b[1])
+    print("case static: first call with a shape recorded into a graph", flush=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        D.dynamix_grad_aggregate_stats_static(wa.grads, wa.batch_sizes, out_agg=agg_a,
+                                              out_stats=st_a, stream=torch.cuda.current_stream())
+    for rep in range(3):
+        print("case static: replay", rep, flush=True)
+        agg_a.fill_(7.0)
+        st_a.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(agg_a, ref_a[0]) and torch.equal(st_a, ref_a[1]), rep
+        # an eager call of another shape in between overwrites the array's tables
+        D.dynamix_grad_aggregate_stats_static(wb.grads, wb.batch_sizes, out_agg=agg_b, out_stats=st_b)
+        torch.cuda.synchronize()
+        assert torch.equal(agg_b, ref_b[0]) and torch.equal(st_b, ref_b[1]), rep
+    # an eager call of the recorded shape after all that
+    agg_a.fill_(7.0)
+    D.dynamix_grad_aggregate_stats_static(wa.grads, wa.batch_sizes, out_agg=agg_a, out_stats=st_a)
+    torch.cuda.synchronize()
+    assert torch.equal(agg_a, ref_a[0]) and torch.equal(st_a, ref_a[1])
