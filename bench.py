@@ -21,9 +21,9 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 # HBM bytes per launch of the streaming pass from rocprofv3 counters (FETCH_SIZE + WRITE_SIZE,
 # each scaled by the reading of a plain copy of known size), keyed by workload, and the hash of
 # the kernel source they were taken on.  A changed kernel makes the figure stale: traffic = null.
-MEASURED_TRAFFIC = {"C4": {"bytes": 18218519365, "kernel": "5d19c3aefdb8a8f2"},
-                    "C3": {"bytes": 922856609, "kernel": "5d19c3aefdb8a8f2"},
-                    "C5": {"bytes": 4466052918, "kernel": "5d19c3aefdb8a8f2"}}
+MEASURED_TRAFFIC = {"C4": {"bytes": 18218544120, "kernel": "9a0ba85c62a2bcc9"},
+                    "C3": {"bytes": 922842482, "kernel": "9a0ba85c62a2bcc9"},
+                    "C5": {"bytes": 4466021018, "kernel": "9a0ba85c62a2bcc9"}}
 KERNEL_FILES = ("stream_pass.h", "dynamix_internal.h", "stream_pass_inst.hip")
 
 
