@@ -321,9 +321,12 @@ double  dynamix_discounted_return(const double* rewards, int64_t count, double g
  * the two kernels, after the final reduction.  dynamix_timing_count() is the number of slots
  * used.  Once the stream has been synchronised, dynamix_timing_read(i, ...) returns the two
  * kernel durations of the i-th timed call in milliseconds (DYNAMIX_ERR_HIP if that call has not
- * finished, DYNAMIX_ERR_ARG for an unused slot).
+ * finished, DYNAMIX_ERR_ARG for an unused slot).  The events themselves cost the stream about ten
+ * microseconds per timed call; dynamix_timing_every(n) has only every n-th call timed, counted
+ * from the dynamix_timing_begin that follows (n >= 1; the default is every call).
  */
 int     dynamix_timing_begin(int32_t capacity);
+int     dynamix_timing_every(int32_t n);
 int32_t dynamix_timing_count(void);
 int     dynamix_timing_read(int32_t index, float* stream_pass_ms, float* final_reduce_ms);
 

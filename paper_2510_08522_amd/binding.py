@@ -68,6 +68,8 @@ def load():
     lib.dynamix_plan_describe.argtypes = [i32, i64, i32, vp, i64, i64, vp, i64]
     lib.dynamix_timing_begin.restype = ctypes.c_int
     lib.dynamix_timing_begin.argtypes = [i32]
+    lib.dynamix_timing_every.restype = ctypes.c_int
+    lib.dynamix_timing_every.argtypes = [i32]
     lib.dynamix_timing_count.restype = i32
     lib.dynamix_timing_count.argtypes = []
     lib.dynamix_timing_read.restype = ctypes.c_int
@@ -149,6 +151,12 @@ def dynamix_plan_describe(K, P, dtype, segment_offsets=None, max_blocks=256):
 
 def dynamix_timing_begin(capacity):
     rc = int(load().dynamix_timing_begin(int(capacity)))
+    if rc != DYNAMIX_OK:
+        raise DynamixError(rc)
+
+
+def dynamix_timing_every(n):
+    rc = int(load().dynamix_timing_every(int(n)))
     if rc != DYNAMIX_OK:
         raise DynamixError(rc)
 

@@ -108,6 +108,8 @@ struct Timing {
     std::vector<hipEvent_t> events;  // 3 per slot
     int capacity = 0;
     int used = 0;
+    int every = 1;       // only every n-th call is timed (events cost the stream a few microseconds)
+    int64_t calls = 0;   // calls seen since timing began
 };
 Timing g_timing;
 
@@ -610,7 +612,8 @@ int run(const void* const* grads, const int32_t* batch_sizes, int32_t K, int64_t
     fa.K = K;
 
     hipEvent_t* ev = nullptr;
-    if (g_timing.used < g_timing.capacity) ev = &g_timing.events[3 * (size_t)g_timing.used++];
+    if (g_timing.used < g_timing.capacity && g_timing.calls++ % g_timing.every == 0)
+        ev = &g_timing.events[3 * (size_t)g_timing.used++];
     if (ev && hipEventRecord(ev[0], stream) != hipSuccess) return DYNAMIX_ERR_HIP;
     if (launch_stream_pass(K, dtype, up.opt, pl->grid, sa, stream) != hipSuccess) return DYNAMIX_ERR_HIP;
     // From here on the tail counter is in use; only the final reduction sets it back.  Should
@@ -819,6 +822,7 @@ int dynamix_timing_begin(int32_t capacity)
     for (hipEvent_t e : t.events) (void)hipEventDestroy(e);
     t.events.clear();
     t.capacity = t.used = 0;
+    t.calls = 0;
     try {
         t.events.reserve(3 * (size_t)capacity);
     } catch (...) {
@@ -830,6 +834,15 @@ int dynamix_timing_begin(int32_t capacity)
         t.events.push_back(e);
     }
     t.capacity = capacity;
+    return DYNAMIX_OK;
+}
+
+int dynamix_timing_every(int32_t n)
+{
+    if (n < 1) return DYNAMIX_ERR_ARG;
+    std::lock_guard<std::mutex> lock(dynamix::g_mutex);
+    dynamix::g_timing.every = n;
+    dynamix::g_timing.calls = 0;
     return DYNAMIX_OK;
 }
 

@@ -392,6 +392,14 @@ def test_kernel_timing_slots():
         assert 0.0 < t_stream < 50.0 and 0.0 < t_final < 50.0
     with pytest.raises(D.DynamixError):
         D.dynamix_timing_read(2)
+    # only every third call timed: calls 0, 3 and 6 of seven
+    D.dynamix_timing_every(3)
+    D.dynamix_timing_begin(10)
+    for _ in range(7):
+        run_gpu(w)
+    assert D.dynamix_timing_count() == 3
+    assert all(0.0 < D.dynamix_timing_read(i)[0] < 50.0 for i in range(3))
+    D.dynamix_timing_every(1)
     D.dynamix_timing_begin(0)
     assert D.dynamix_timing_count() == 0
 
