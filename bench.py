@@ -138,7 +138,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "wide"],
+                    help="one of the five named configurations, or 'wide': --workers (more than 64: "
+                         "the two-sweep kernel) fp32 buffers of --elements, C4's generator")
+    ap.add_argument("--workers", type=int, default=128)
+    ap.add_argument("--elements", type=int, default=34_500_000)
+    ap.add_argument("--update", default="none", choices=["none", "sgd", "momentum", "adam"],
+                    help="time the pass with this model update fused in instead of the write of the "
+                         "aggregate (momentum, adam: up to 32 workers)")
     ap.add_argument("--cpu-sample", type=int, default=16_000_000,
                     help="elements per worker the CPU oracle is timed on (0: skip)")
     ap.add_argument("--cpu-threads", type=int, default=16)
@@ -177,9 +184,18 @@ def main():
     D.binding.load()                      # no fallback: raises if the library cannot be loaded
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    w = W.config(args.workload, device=dev, one_allocation=args.one_allocation,
-                 stagger_elems=0 if args.one_allocation else args.stagger_elems)
-    out_agg = torch.empty(w.P, dtype=torch.float32, device=dev)
+    if args.workload == "wide":
+        import numpy as np
+        seed = W.BASE_SEED + 6
+        b = np.random.default_rng(seed).integers(16, 257, size=args.workers)
+        w = W.make(args.workers, args.elements, torch.float32, b, 1e-3, 1e-2, seed, device=dev,
+                   name="wide", one_allocation=args.one_allocation)
+    else:
+        w = W.config(args.workload, device=dev, one_allocation=args.one_allocation,
+                     stagger_elems=0 if args.one_allocation else args.stagger_elems)
+    # streams the pass writes per element (and, but for the plain aggregate, reads first)
+    n_state = {"none": 0, "sgd": 1, "momentum": 2, "adam": 3}[args.update]
+    out_agg = torch.zeros(w.P, dtype=torch.float32, device=dev)
     out_stats = torch.empty((1 + w.S, D.DYNAMIX_STATS_HEAD + 2 * w.K), dtype=torch.float64,
                             device=dev)
     stream = torch.cuda.current_stream()
@@ -187,6 +203,7 @@ def main():
     # Cold-cache protocol: a workload that the 256 MB memory-side cache could hold between steps
     # is timed on a rotation of copies at distinct addresses, together more than twice the cache.
     CACHE = 256 << 20
+    state = [torch.zeros(w.P, dtype=torch.float32, device=dev) for _ in range(max(0, n_state - 1))]
     sets = [(w.grads, out_agg)]
     if w.bytes_read + w.P * 4 > 2 * CACHE:
         cache_note = "cold by size: one step streams %.0f MB through a 256 MB cache" % (
@@ -196,16 +213,29 @@ def main():
     else:
         copies = -(-(5 * CACHE // 2) // (w.bytes_read + w.P * 4))
         for _ in range(copies - 1):
-            sets.append(([g.clone() for g in w.grads], torch.empty_like(out_agg)))
+            sets.append(([g.clone() for g in w.grads], torch.zeros_like(out_agg)))
         cache_note = "cold: rotation of %d copies of the inputs at distinct addresses (%.0f MB)" % (
             copies, copies * (w.bytes_read + w.P * 4) / 1e6)
     calls = [0]
 
     def step():
+        # (with a fused update the set's output buffer serves as the parameter vector)
         grads, agg = sets[calls[0] % len(sets)]
         calls[0] += 1
-        D.dynamix_grad_aggregate_stats_ex(grads, w.batch_sizes, w.segment_offsets,
-                                          out_agg=agg, out_stats=out_stats, stream=stream)
+        if args.update == "none":
+            D.dynamix_grad_aggregate_stats_ex(grads, w.batch_sizes, w.segment_offsets,
+                                              out_agg=agg, out_stats=out_stats, stream=stream)
+        elif args.update == "sgd":
+            D.dynamix_grad_aggregate_stats_sgd(grads, w.batch_sizes, agg, 0.01, 1e-4,
+                                               w.segment_offsets, out_stats=out_stats, stream=stream)
+        elif args.update == "momentum":
+            D.dynamix_grad_aggregate_stats_sgd_momentum(grads, w.batch_sizes, agg, state[0], 0.01, 1e-4,
+                                                        0.9, False, w.segment_offsets,
+                                                        out_stats=out_stats, stream=stream)
+        else:
+            D.dynamix_grad_aggregate_stats_adam(grads, w.batch_sizes, agg, state[0], state[1], 1e-3,
+                                                calls[0], segment_offsets=w.segment_offsets,
+                                                out_stats=out_stats, stream=stream)
 
     if args.calibrate_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -257,12 +287,14 @@ def main():
 
     ms_per_step = elapsed / args.steps * 1e3
     read_bytes = w.bytes_read
-    algo_bytes = read_bytes + w.P * 4                    # K*s read + 4 written per element
+    sweeps = 2 if w.K > D.DYNAMIX_K_MAX_ONE_SWEEP else 1 # above 64 workers the gradients are read twice
+    # K*s read + 4 written per element; a fused update reads and writes 4 per element and stream
+    algo_bytes = sweeps * read_bytes + w.P * 4 * (1 if n_state == 0 else 2 * n_state)
     value = read_bytes / (elapsed / args.steps) / 1e9
     achieved = algo_bytes / k_stream / 1e9
     ns = float(out_stats[0, D.STAT["noise_scale"]].item())
 
-    m = MEASURED_TRAFFIC.get(w.name)
+    m = MEASURED_TRAFFIC.get(w.name) if args.update == "none" else None
     traffic = m["bytes"] if m and m["kernel"] == kernel_source_hash() else None
 
     line = {
@@ -278,7 +310,9 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",      # accumulation type; bf16 inputs are widened exactly
         "data": "synthetic",
-        "config": {"workload": describe(w), "K": w.K, "P": w.P, "segments": w.S,
+        "config": {"workload": describe(w) + ("" if args.update == "none" else
+                                              ", fused %s update" % args.update),
+                   "K": w.K, "P": w.P, "segments": w.S, "update": args.update,
                    "input_dtype": "bf16" if w.itemsize == 2 else "fp32",
                    "bytes_read_per_step": read_bytes, "seed": w.seed,
                    "buffers": ("K allocations" + (", staggered by %d elements" % args.stagger_elems
@@ -291,7 +325,7 @@ def main():
         "noise_scale": ns,
         "host_enqueue_us_per_step": round(enqueued / args.steps * 1e6, 2),
         "settle_seconds": args.settle_seconds,
-        "roofline": {"bound": "hbm", "kernel": "stream_pass_kernel",
+        "roofline": {"bound": "hbm", "kernel": "wide_pass_kernel" if sweeps == 2 else "stream_pass_kernel",
                      "achieved": round(achieved, 2), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                      "algorithmic_bytes_per_launch": algo_bytes,
@@ -303,7 +337,7 @@ def main():
     line["stats_only"] = {"kernel_ms": round(so_ms, 5),
                           "read_GBps": round(read_bytes / so_ms / 1e6, 2),
                           "frac_of_peak": round(read_bytes / so_ms / 1e6 / HBM_PEAK_GBPS, 4)}
-    ceiling = memory_ceiling(D, torch, sets, w, stream)
+    ceiling = memory_ceiling(D, torch, sets, w, stream) if args.update == "none" else None
     if ceiling:
         line["memory_ceiling"] = ceiling
     if args.cpu_sample > 0:
