@@ -298,9 +298,23 @@ int64_t dynamix_cycle_summary_count(int32_t K, int64_t num_segments);
  *   means from dynamix_cycle_summary (global record, entries DYNAMIX_STAT_SIGMA2_NORM and
  *   DYNAMIX_STAT_SIGMA_NORM of the means), used only when adaptive_optimizer != 0.
  * dynamix_discounted_return: sum_t gamma^t rewards[t] over count cycles.
+ * dynamix_policy_update: one gradient-ascent step of the shared parameters on n recorded
+ *   decisions (Algorithm 1, the policy-update step), weights <- weights + lr * gradient of the
+ *   mean objective, evaluated before the step and returned in *objective (may be NULL):
+ *     DYNAMIX_POLICY_RETURN_WEIGHTED  mean_j signal[j] log pi(a_j | s_j): the paper's simplified
+ *                                     rule, the cumulative reward as the weight of each decision,
+ *                                     no clipping and no advantage estimate; old_probs unused
+ *     DYNAMIX_POLICY_CLIPPED          mean_j min(r_j signal[j], clip(r_j, 1-eps, 1+eps) signal[j]),
+ *                                     r_j = pi(a_j | s_j) / old_probs[j], the clipped surrogate
+ *                                     of the paper's PPO objective with signal = the advantage
+ *   states: n rows as for dynamix_policy_forward; actions: n indices; signal: n doubles;
+ *   old_probs: n probabilities the old policy gave the taken actions.  Gradients by
+ *   back-propagation in double; the optimizer around it (learning-rate schedule, epochs over the
+ *   batch) is the caller's.
  * All return a dynamix_status except the two that return a count or a value.
  */
 enum { DYNAMIX_NUM_ACTIONS = 5 };
+enum { DYNAMIX_POLICY_RETURN_WEIGHTED = 0, DYNAMIX_POLICY_CLIPPED = 1 };
 #define DYNAMIX_ACTIONS {-100, -25, 0, 25, 100}
 int64_t dynamix_policy_weight_count(const int32_t* layer_sizes, int32_t num_layers);
 int     dynamix_policy_forward(const float* weights, const int32_t* layer_sizes, int32_t num_layers,
@@ -313,6 +327,10 @@ int     dynamix_cycle_rewards(const double* mean_accuracy, const double* accurac
                               double alpha, double beta, double delta, double eta, double sigma2_norm,
                               double sigma_norm, int32_t adaptive_optimizer, double* rewards);
 double  dynamix_discounted_return(const double* rewards, int64_t count, double gamma);
+int     dynamix_policy_update(float* weights, const int32_t* layer_sizes, int32_t num_layers,
+                              const float* states, const int32_t* actions, const double* signal,
+                              const float* old_probs, int64_t n, int32_t mode, double clip_eps,
+                              double lr, double* objective);
 
 /*
  * Kernel timing (profiling aid).  dynamix_timing_begin(capacity) creates `capacity` slots of HIP

@@ -80,3 +80,57 @@ def rewards(mean_acc, acc_gain, t_iter, batch_sizes, alpha, beta, delta, eta=0.0
 
 def discounted_return(r, gamma):
     return sum(gamma ** t * x for t, x in enumerate(r))
+
+
+def objective(weights, layer_sizes, states, actions, signal, old_probs=None, clip_eps=0.2):
+    """Mean over the recorded decisions of signal * log pi(a | s) (the paper's simplified rule:
+    the cumulative reward weighs each decision) or, with old_probs, of the clipped surrogate
+    min(r A, clip(r, 1 - eps, 1 + eps) A), r = pi(a | s) / old_prob (the PPO objective, Eq. 1)."""
+    p = policy_probs(weights, layer_sizes, states)
+    total = 0.0
+    for j, a in enumerate(actions):
+        if old_probs is None:
+            total += signal[j] * np.log(p[j, a])
+        else:
+            r = p[j, a] / float(old_probs[j])
+            total += min(r * signal[j], min(max(r, 1 - clip_eps), 1 + clip_eps) * signal[j])
+    return total / len(actions)
+
+
+def objective_gradient(weights, layer_sizes, states, actions, signal, old_probs=None, clip_eps=0.2):
+    """Gradient of `objective` with respect to the flat parameter vector, by the chain rule written
+    out layer by layer (float64)."""
+    layers = unpack(weights, layer_sizes)
+    grads = [(np.zeros_like(W), np.zeros_like(b)) for W, b in layers]
+    n = len(actions)
+    for j, a in enumerate(actions):
+        hs = [np.asarray(states[j], dtype=np.float64)]
+        for i, (W, b) in enumerate(layers):
+            z = W @ hs[-1] + b
+            hs.append(np.tanh(z) if i + 1 < len(layers) else z)
+        e = np.exp(hs[-1] - hs[-1].max())
+        p = e / e.sum()
+        onehot = np.zeros(len(p))
+        onehot[a] = 1.0
+        if old_probs is None:
+            scale = signal[j]                       # d(R log p_a)/dz = R (onehot - p)
+        else:
+            r = p[a] / float(old_probs[j])
+            held = min(max(r, 1 - clip_eps), 1 + clip_eps)
+            # the minimum moves with r only where the unclipped term is the smaller one
+            scale = signal[j] * r if r * signal[j] <= held * signal[j] else 0.0
+        delta = scale * (onehot - p) / n
+        for i in range(len(layers) - 1, -1, -1):
+            W, _ = layers[i]
+            grads[i][0][...] += np.outer(delta, hs[i])
+            grads[i][1][...] += delta
+            delta = W.T @ delta
+            if i > 0:
+                delta = delta * (1.0 - hs[i] ** 2)  # tanh'
+    return np.concatenate([np.concatenate([gW.ravel(), gb]) for gW, gb in grads])
+
+
+def update(weights, layer_sizes, states, actions, signal, lr, old_probs=None, clip_eps=0.2):
+    """One ascent step; returns the new flat parameters (float64)."""
+    g = objective_gradient(weights, layer_sizes, states, actions, signal, old_probs, clip_eps)
+    return np.asarray(weights, dtype=np.float64) + lr * g

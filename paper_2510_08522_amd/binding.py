@@ -94,6 +94,8 @@ def load():
     lib.dynamix_batch_sizes_step.argtypes = [vp, vp, i32, i32, i32, vp]
     lib.dynamix_cycle_rewards.restype = ctypes.c_int
     lib.dynamix_cycle_rewards.argtypes = [vp, vp, vp, vp, i32, f64, f64, f64, f64, f64, f64, i32, vp]
+    lib.dynamix_policy_update.restype = ctypes.c_int
+    lib.dynamix_policy_update.argtypes = [vp, vp, i32, vp, vp, vp, vp, i64, i32, f64, f64, vp]
     lib.dynamix_discounted_return.restype = f64
     lib.dynamix_discounted_return.argtypes = [vp, i64, f64]
     lib.dynamix_release_cached.restype = ctypes.c_int
@@ -449,3 +451,27 @@ def dynamix_cycle_rewards(mean_accuracy, accuracy_gain, iteration_time, batch_si
 def dynamix_discounted_return(rewards, gamma):
     r = _np(rewards, np.float64)
     return float(load().dynamix_discounted_return(r.ctypes.data, len(r), float(gamma)))
+
+
+DYNAMIX_POLICY_RETURN_WEIGHTED, DYNAMIX_POLICY_CLIPPED = 0, 1
+
+
+def dynamix_policy_update(weights, layer_sizes, states, actions, signal, lr, old_probs=None,
+                          clip_eps=0.2):
+    """One ascent step on n recorded decisions; returns (new weights float32, objective before the
+    step).  With old_probs the clipped surrogate (signal = advantages), else the return-weighted
+    log-likelihood (signal = cumulative rewards)."""
+    ls = _np(layer_sizes, np.int32)
+    w = _np(weights, np.float32).copy()
+    st, a, sg = _np(states, np.float32), _np(actions, np.int32), _np(signal, np.float64)
+    if st.ndim != 2 or st.shape[1] != ls[0] or len(a) != st.shape[0] or len(sg) != st.shape[0] \
+            or w.size != dynamix_policy_weight_count(ls):
+        raise ValueError("states [n, layer_sizes[0]], actions [n], signal [n] and matching weights")
+    op = None if old_probs is None else _np(old_probs, np.float32)
+    obj = ctypes.c_double()
+    _check(int(load().dynamix_policy_update(
+        w.ctypes.data, ls.ctypes.data, len(ls), st.ctypes.data, a.ctypes.data, sg.ctypes.data,
+        None if op is None else op.ctypes.data, st.shape[0],
+        DYNAMIX_POLICY_RETURN_WEIGHTED if op is None else DYNAMIX_POLICY_CLIPPED, float(clip_eps),
+        float(lr), ctypes.byref(obj))))
+    return w, obj.value

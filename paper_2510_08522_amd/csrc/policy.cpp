@@ -128,6 +128,91 @@ int dynamix_cycle_rewards(const double* mean_accuracy, const double* accuracy_ga
     return DYNAMIX_OK;
 }
 
+int dynamix_policy_update(float* weights, const int32_t* layer_sizes, int32_t num_layers,
+                          const float* states, const int32_t* actions, const double* signal,
+                          const float* old_probs, int64_t n, int32_t mode, double clip_eps, double lr,
+                          double* objective)
+{
+    if (!weights || !layer_sizes || !states || !actions || !signal) return DYNAMIX_ERR_NULL;
+    if (mode == DYNAMIX_POLICY_CLIPPED && !old_probs) return DYNAMIX_ERR_NULL;
+    const int64_t count = dynamix_policy_weight_count(layer_sizes, num_layers);
+    if (n < 1 || count < 0 || layer_sizes[num_layers - 1] != DYNAMIX_NUM_ACTIONS ||
+        (mode != DYNAMIX_POLICY_RETURN_WEIGHTED && mode != DYNAMIX_POLICY_CLIPPED) ||
+        !(clip_eps >= 0.0) || !(lr == lr))
+        return DYNAMIX_ERR_ARG;
+    for (int64_t j = 0; j < n; ++j)
+        if (actions[j] < 0 || actions[j] >= DYNAMIX_NUM_ACTIONS) return DYNAMIX_ERR_ARG;
+    try {
+        const int L = num_layers - 1;   // weight layers
+        std::vector<double> grad((size_t)count, 0.0);
+        std::vector<std::vector<double>> act(num_layers);   // activations of every layer
+        for (int l = 0; l < num_layers; ++l) act[l].assign(layer_sizes[l], 0.0);
+        std::vector<double> delta, prev;
+        double total = 0.0;
+        for (int64_t j = 0; j < n; ++j) {
+            // forward, keeping the activations
+            for (int i = 0; i < layer_sizes[0]; ++i) act[0][i] = states[j * layer_sizes[0] + i];
+            const float* w = weights;
+            for (int l = 0; l < L; ++l) {
+                const int in = layer_sizes[l], out = layer_sizes[l + 1];
+                const float* bias = w + (int64_t)out * in;
+                for (int o = 0; o < out; ++o) {
+                    double s = bias[o];
+                    for (int i = 0; i < in; ++i) s += (double)w[(int64_t)o * in + i] * act[l][i];
+                    act[l + 1][o] = l + 1 < L ? std::tanh(s) : s;
+                }
+                w = bias + out;
+            }
+            const std::vector<double>& z = act[L];
+            double top = z[0];
+            for (int a = 1; a < DYNAMIX_NUM_ACTIONS; ++a) top = std::max(top, z[a]);
+            double p[DYNAMIX_NUM_ACTIONS], zsum = 0.0;
+            for (int a = 0; a < DYNAMIX_NUM_ACTIONS; ++a) zsum += p[a] = std::exp(z[a] - top);
+            for (int a = 0; a < DYNAMIX_NUM_ACTIONS; ++a) p[a] /= zsum;
+            const int aj = actions[j];
+            // d(objective_j)/d(logit) = scale * (onehot(a_j) - p)
+            double scale;
+            if (mode == DYNAMIX_POLICY_RETURN_WEIGHTED) {
+                total += signal[j] * std::log(p[aj]);
+                scale = signal[j];
+            } else {
+                const double r = p[aj] / (double)old_probs[j];
+                const double clipped = std::min(std::max(r, 1.0 - clip_eps), 1.0 + clip_eps);
+                const double plain = r * signal[j], held = clipped * signal[j];
+                total += std::min(plain, held);
+                // the minimum follows r only where the unclipped term is the smaller one
+                scale = plain <= held ? signal[j] * r : 0.0;
+            }
+            delta.assign(DYNAMIX_NUM_ACTIONS, 0.0);
+            for (int a = 0; a < DYNAMIX_NUM_ACTIONS; ++a) delta[a] = scale * ((a == aj ? 1.0 : 0.0) - p[a]);
+            // backward through the layers (offsets of layer l's parameters inside the flat vector)
+            int64_t end = count;
+            for (int l = L - 1; l >= 0; --l) {
+                const int in = layer_sizes[l], out = layer_sizes[l + 1];
+                const int64_t wofs = end - ((int64_t)out * in + out), bofs = wofs + (int64_t)out * in;
+                prev.assign(in, 0.0);
+                for (int o = 0; o < out; ++o) {
+                    grad[bofs + o] += delta[o];
+                    for (int i = 0; i < in; ++i) {
+                        grad[wofs + (int64_t)o * in + i] += delta[o] * act[l][i];
+                        prev[i] += delta[o] * (double)weights[wofs + (int64_t)o * in + i];
+                    }
+                }
+                if (l > 0)   // through the tanh of layer l's input
+                    for (int i = 0; i < in; ++i) prev[i] *= 1.0 - act[l][i] * act[l][i];
+                delta.swap(prev);
+                end = wofs;
+            }
+        }
+        if (objective) *objective = total / (double)n;
+        const double step = lr / (double)n;   // ascent on the mean over the n decisions
+        for (int64_t i = 0; i < count; ++i) weights[i] = (float)((double)weights[i] + step * grad[i]);
+    } catch (...) {
+        return DYNAMIX_ERR_NOMEM;
+    }
+    return DYNAMIX_OK;
+}
+
 double dynamix_discounted_return(const double* rewards, int64_t count, double gamma)
 {
     if (!rewards || count < 1) return 0.0;

@@ -156,3 +156,97 @@ def test_a_cycle_end_to_end_on_the_host():
     assert ((nxt >= 32) & (nxt <= 1024)).all()
     for before, after in zip(b.tolist(), nxt.tolist()):     # a listed move, or a clamped one
         assert after in {min(max(before + a, 32), 1024) for a in O.ACTIONS}
+
+
+# ------------------------------------------------------------------ the policy update
+def decisions(seed, sizes, n):
+    rng = np.random.default_rng(seed)
+    w = network(seed, sizes).astype(np.float64)
+    states = rng.standard_normal((n, sizes[0]))
+    actions = rng.integers(0, 5, size=n)
+    signal = rng.standard_normal(n) * 2.0
+    old = O.policy_probs(w, sizes, states)[np.arange(n), actions] * np.exp(rng.uniform(-0.4, 0.4, n))
+    return w, states, actions, signal, np.minimum(old, 0.99)
+
+
+def torch_objective(w, sizes, states, actions, signal, old=None, eps=0.2):
+    """The same objective through a library network and automatic differentiation."""
+    wt = torch.tensor(w, dtype=torch.float64, requires_grad=True)
+    h, pos = torch.from_numpy(np.asarray(states, dtype=np.float64)), 0
+    for i, (n_in, n_out) in enumerate(zip(sizes[:-1], sizes[1:])):
+        W = wt[pos:pos + n_out * n_in].reshape(n_out, n_in)
+        pos += n_out * n_in
+        b = wt[pos:pos + n_out]
+        pos += n_out
+        h = h @ W.T + b
+        if i + 2 < len(sizes):
+            h = torch.tanh(h)
+    logp = torch.log_softmax(h, dim=1)[torch.arange(len(actions)), torch.from_numpy(np.asarray(actions))]
+    sg = torch.from_numpy(np.asarray(signal, dtype=np.float64))
+    if old is None:
+        J = (sg * logp).mean()
+    else:
+        r = torch.exp(logp) / torch.from_numpy(np.asarray(old, dtype=np.float64))
+        J = torch.minimum(r * sg, torch.clamp(r, 1 - eps, 1 + eps) * sg).mean()
+    J.backward()
+    return float(J.detach()), wt.grad.numpy()
+
+
+@pytest.mark.parametrize("sizes", [[3, 5], [6, 8, 5], [4, 7, 6, 5]])
+def test_oracle_gradient_matches_automatic_differentiation(sizes):
+    w, st, a, sg, old = decisions(21, sizes, 40)
+    for o in (None, old):
+        J, g = torch_objective(w, sizes, st, a, sg, o)
+        assert abs(O.objective(w, sizes, st, a, sg, o) - J) < 1e-13
+        np.testing.assert_allclose(O.objective_gradient(w, sizes, st, a, sg, o), g, rtol=1e-10, atol=1e-14)
+
+
+def test_oracle_gradient_closed_forms():
+    # one linear layer, one decision, zero parameters: p = 1/5 everywhere, so the bias gradient of
+    # R log p_a is R (onehot - 1/5) and the matrix gradient its outer product with the state
+    sizes, s, R = [2, 5], np.array([[2.0, -1.0]]), 3.0
+    g = O.objective_gradient(np.zeros(15), sizes, s, [3], [R])
+    want_b = R * (np.eye(5)[3] - 0.2)
+    np.testing.assert_allclose(g[10:], want_b, rtol=1e-15)
+    np.testing.assert_allclose(g[:10].reshape(5, 2), np.outer(want_b, s[0]), rtol=1e-15)
+    # clipped surrogate: with a positive advantage and a ratio above 1 + eps the objective is flat
+    # (gradient zero); with a negative advantage it still follows the ratio
+    old = [0.1]                                     # p = 0.2, r = 2 > 1.2
+    assert not O.objective_gradient(np.zeros(15), sizes, s, [3], [1.0], old).any()
+    gneg = O.objective_gradient(np.zeros(15), sizes, s, [3], [-1.0], old)
+    np.testing.assert_allclose(gneg[10:], -1.0 * 2.0 * (np.eye(5)[3] - 0.2), rtol=1e-15)
+    assert O.objective(np.zeros(15), sizes, s, [3], [1.0], old) == 1.2
+    assert O.objective(np.zeros(15), sizes, s, [3], [-1.0], old) == -2.0
+    # inside the clip range the two terms coincide: gradient A r (onehot - p)
+    gin = O.objective_gradient(np.zeros(15), sizes, s, [3], [1.0], [0.2])
+    np.testing.assert_allclose(gin[10:], np.eye(5)[3] - 0.2, rtol=1e-15)
+
+
+def test_oracle_gradient_against_finite_differences():
+    sizes = [5, 6, 5]
+    w, st, a, sg, old = decisions(22, sizes, 16)
+    g = O.objective_gradient(w, sizes, st, a, sg)
+    rng = np.random.default_rng(0)
+    for i in rng.choice(len(w), size=12, replace=False):
+        e = np.zeros_like(w)
+        e[i] = 1e-6
+        fd = (O.objective(w + e, sizes, st, a, sg) - O.objective(w - e, sizes, st, a, sg)) / 2e-6
+        assert abs(fd - g[i]) < 1e-7 * max(1.0, abs(g[i]))
+
+
+@pytest.mark.parametrize("sizes", [[3, 5], [9, 16, 5], [6, 12, 8, 5]])
+def test_library_policy_update(sizes):
+    w, st, a, sg, old = decisions(23, sizes, 64)
+    w32 = w.astype(np.float32)
+    st32, old32 = st.astype(np.float32), old.astype(np.float32)
+    for o in (None, old32):
+        new, J = D.dynamix_policy_update(w32, sizes, st32, a, sg, 0.05, old_probs=o)
+        want = O.update(w32, sizes, st32, a, sg, 0.05, o)
+        assert abs(J - O.objective(w32, sizes, st32, a, sg, o)) < 1e-12
+        np.testing.assert_allclose(new, want, rtol=2e-7, atol=1e-8)
+        assert np.abs(new - w32).max() > 1e-4                   # it did move
+    # ascent: a small step on the return-weighted objective does not lower it
+    new, J0 = D.dynamix_policy_update(w32, sizes, st32, a, sg, 1e-3)
+    assert O.objective(new, sizes, st32, a, sg) >= J0
+    with pytest.raises(D.DynamixError):
+        D.dynamix_policy_update(w32, sizes, st32, np.full(64, 5), sg, 0.05)
